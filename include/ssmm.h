@@ -20,7 +20,8 @@
  *   - argument and shape errors are detected on the host before anything is
  *     launched (SSMM_EINVAL: null pointer or bad scalar; SSMM_ESHAPE: a size
  *     the format or the kernels do not admit; SSMM_EWORKSPACE: workspace too
- *     small; SSMM_EHIP: the HIP runtime reported a launch error).
+ *     small; SSMM_EHIP: the HIP runtime reported a launch error; SSMM_ELIMIT: a
+ *     size beyond the fixed scratch of an entry point that takes no workspace).
  *   - weight matrices are given as the transposed operand A = W^T of section
  *     4.5: `rows` output features by `K` reduction elements, row-major.
  */
@@ -39,7 +40,8 @@ typedef enum {
   SSMM_EINVAL = -1,
   SSMM_ESHAPE = -2,
   SSMM_EWORKSPACE = -3,
-  SSMM_EHIP = -4
+  SSMM_EHIP = -4,
+  SSMM_ELIMIT = -5
 } ssmm_status;
 
 /* The expert's activation function (the paper names none: sections 2.1, 4.5; its models use
@@ -177,6 +179,22 @@ int ssmm_route_bucket(const float* logits, int T, int E, int topk, int n_shared,
                       int32_t* topk_ids, float* topk_w, int32_t* expert_offsets, int32_t* sel,
                       float* sel_w, int32_t* inv, void* workspace, size_t workspace_bytes,
                       void* stream);
+
+/*
+ * ssmm_route_bucket for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments (without the workspace), same kernels, same outputs bit for
+ * bit.  The per-chunk histograms the kernels keep between their launches live in a fixed
+ * 256 KiB array inside the library, one copy per GPU, held until the process ends; the
+ * call allocates and frees nothing and calls no allocating routine.
+ * Limit: ceil(T / 256) * E <= 65536 (e.g. 65536 tokens with 256 experts, 262144 with 64);
+ * beyond it the call returns SSMM_ELIMIT and launches nothing.  Every call on a GPU uses
+ * that GPU's one array: calls that overlap on one GPU (two streams, two host threads) race
+ * and must be serialised by the caller; nothing in the array needs clearing between calls.
+ */
+int ssmm_route_bucket_noalloc(const float* logits, int T, int E, int topk, int n_shared, int renormalize,
+                              int32_t* topk_ids, float* topk_w, int32_t* expert_offsets, int32_t* sel,
+                              float* sel_w, int32_t* inv, void* stream);
 
 /*
  * The expert FFNs of one MoE layer as sparse-sparse matrix multiplications

@@ -15,7 +15,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("SSMM_LIB_PATH", os.path.join(_PKG, "libssmm.so"))   # override: tuning builds
 
-SSMM_OK, SSMM_EINVAL, SSMM_ESHAPE, SSMM_EWORKSPACE, SSMM_EHIP = 0, -1, -2, -3, -4
+SSMM_OK, SSMM_EINVAL, SSMM_ESHAPE, SSMM_EWORKSPACE, SSMM_EHIP, SSMM_ELIMIT = 0, -1, -2, -3, -4, -5
 
 
 class Format(ctypes.Structure):
@@ -46,6 +46,8 @@ EXPORTS = {
     "ssmm_route_workspace_bytes": (c_size_t, [c_int, c_int, c_int, c_int]),
     "ssmm_route_bucket": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p,
                                   c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "ssmm_route_bucket_noalloc": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p,
+                                          c_void_p, c_void_p, c_void_p, c_void_p]),
     "ssmm_router_logits": (c_int, [c_void_p, c_int, c_int, c_void_p, c_int, c_void_p, c_void_p]),
     "ssmm_ffn_workspace_bytes": (c_size_t, [c_int, c_int, c_int, c_int, c_int, Format]),
     "ssmm_expert_ffn": (c_int, [c_void_p, c_int, c_int, c_int, c_int, Format, c_void_p, c_void_p, c_void_p,
@@ -193,6 +195,17 @@ def route_bucket(logits, topk, n_shared, renormalize, buf: RouteBuffers = None):
                                    _ptr(buf.topk_ids), _ptr(buf.topk_w), _ptr(buf.expert_offsets), _ptr(buf.sel),
                                    _ptr(buf.sel_w), _ptr(buf.inv), _ptr(buf.workspace), buf.workspace.numel(),
                                    _stream()), "ssmm_route_bucket")
+    return buf
+
+
+def route_bucket_noalloc(logits, topk, n_shared, renormalize, buf: RouteBuffers):
+    """route_bucket through the entry point that takes no workspace and allocates nothing:
+    every output tensor of `buf` must exist already (its workspace is not used)."""
+    T, E = logits.shape
+    _check(lib().ssmm_route_bucket_noalloc(_ptr(logits, torch.float32), T, E, topk, n_shared, int(bool(renormalize)),
+                                           _ptr(buf.topk_ids), _ptr(buf.topk_w), _ptr(buf.expert_offsets),
+                                           _ptr(buf.sel), _ptr(buf.sel_w), _ptr(buf.inv), _stream()),
+           "ssmm_route_bucket_noalloc")
     return buf
 
 

@@ -264,6 +264,7 @@ extern "C" const char* ssmm_strerror(int status) {
     case SSMM_ESHAPE: return "shape not admitted by the format or the kernels";
     case SSMM_EWORKSPACE: return "workspace too small";
     case SSMM_EHIP: return "HIP runtime error at launch";
+    case SSMM_ELIMIT: return "size beyond the fixed scratch of an entry point that takes no workspace";
     default: return "unknown status";
   }
 }

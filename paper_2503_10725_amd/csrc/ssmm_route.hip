@@ -338,23 +338,13 @@ extern "C" size_t ssmm_route_workspace_bytes(int T, int E, int topk, int n_share
   return ((chunks * (size_t)E * sizeof(int32_t)) + 255) / 256 * 256 + 256;
 }
 
-extern "C" int ssmm_route_bucket(const float* logits, int T, int E, int topk, int n_shared, int renormalize,
-                                 int32_t* topk_ids, float* topk_w, int32_t* expert_offsets, int32_t* sel,
-                                 float* sel_w, int32_t* inv, void* workspace, size_t workspace_bytes,
-                                 void* stream) {
-  if (T < 0 || E < 1 || n_shared < 0) return SSMM_EINVAL;
-  if (topk < 1 || topk > E || topk > kMaxTopk) return SSMM_ESHAPE;
-  if (E + n_shared > kMaxExperts) return SSMM_ESHAPE;
-  if ((int64_t)T * (topk + n_shared) > INT32_MAX) return SSMM_ESHAPE;
-  if (!expert_offsets) return SSMM_EINVAL;
-  hipStream_t s = (hipStream_t)stream;
-  if (T == 0) {
-    hipLaunchKernelGGL(zero_offsets_kernel, dim3(2), dim3(256), 0, s, expert_offsets, E + n_shared + 1);
-    SSMM_RETURN_IF_LAUNCH_FAILED();
-    return SSMM_OK;
-  }
-  if (!logits || !topk_ids || !topk_w || !sel || !sel_w || !inv || !workspace) return SSMM_EINVAL;
-  if (workspace_bytes < ssmm_route_workspace_bytes(T, E, topk, n_shared)) return SSMM_EWORKSPACE;
+namespace ssmm {
+
+// Everything ssmm_route_bucket does, with the per-chunk histogram in `counts`
+// (chunks x E cells; unused up to kSmallT tokens).  Arguments already checked.
+static int launch_route_bucket(const float* logits, int T, int E, int topk, int n_shared, int renormalize,
+                               int32_t* topk_ids, float* topk_w, int32_t* expert_offsets, int32_t* sel, float* sel_w,
+                               int32_t* inv, int32_t* counts, hipStream_t s) {
   if (T <= kSmallT) {
     const int fused_route = T <= 16;   // one token per wavefront (measured: with more, routing them one after the other costs more than a launch)
     if (!fused_route) {
@@ -368,7 +358,6 @@ extern "C" int ssmm_route_bucket(const float* logits, int T, int E, int topk, in
     return SSMM_OK;
   }
   const int chunks = (T + kChunk - 1) / kChunk;
-  int32_t* counts = (int32_t*)workspace;
   hipLaunchKernelGGL(route_kernel, dim3((T + 3) / 4), dim3(256), 0, s, logits, T, E, topk, renormalize, topk_ids,
                      topk_w);
   SSMM_RETURN_IF_LAUNCH_FAILED();
@@ -382,6 +371,81 @@ extern "C" int ssmm_route_bucket(const float* logits, int T, int E, int topk, in
                      sel_w, inv);
   SSMM_RETURN_IF_LAUNCH_FAILED();
   return SSMM_OK;
+}
+
+// Host-side checks shared by the two entry points; SSMM_OK with *done set when nothing is left to do.
+static int check_route_bucket(const float* logits, int T, int E, int topk, int n_shared, int32_t* topk_ids, float* topk_w,
+                              int32_t* expert_offsets, int32_t* sel, float* sel_w, int32_t* inv, hipStream_t s, bool* done) {
+  *done = false;
+  if (T < 0 || E < 1 || n_shared < 0) return SSMM_EINVAL;
+  if (topk < 1 || topk > E || topk > kMaxTopk) return SSMM_ESHAPE;
+  if (E + n_shared > kMaxExperts) return SSMM_ESHAPE;
+  if ((int64_t)T * (topk + n_shared) > INT32_MAX) return SSMM_ESHAPE;
+  if (!expert_offsets) return SSMM_EINVAL;
+  if (T == 0) {
+    hipLaunchKernelGGL(zero_offsets_kernel, dim3(2), dim3(256), 0, s, expert_offsets, E + n_shared + 1);
+    SSMM_RETURN_IF_LAUNCH_FAILED();
+    *done = true;
+    return SSMM_OK;
+  }
+  if (!logits || !topk_ids || !topk_w || !sel || !sel_w || !inv) return SSMM_EINVAL;
+  return SSMM_OK;
+}
+
+// ---- the entry point that allocates nothing and takes no workspace -------------------------
+// Its per-chunk histogram lives in this array, one copy per GPU, held until the process ends.
+constexpr int kStaticCells = 65536;   // (chunks of 256 tokens) x E cells of 4 bytes: 256 KiB
+static __device__ __align__(256) int32_t scratch[kStaticCells];
+
+// In host code `scratch` is a stand-in, not a device address.  The device address is asked for
+// once per device, with that device current, and kept; only that pointer goes to kernels.
+constexpr int kMaxDevices = 64;
+static int32_t* scratch_ptr[kMaxDevices];
+static int scratch_of_current_device(int32_t** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SSMM_EHIP;
+  int32_t* p = __atomic_load_n(&scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!p) {
+    void* addr = nullptr;
+    if (hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch)) != hipSuccess || !addr) return SSMM_EHIP;
+    p = (int32_t*)addr;   // every thread that gets here is given the same address for this device
+    __atomic_store_n(&scratch_ptr[dev], p, __ATOMIC_RELEASE);
+  }
+  *out = p;
+  return SSMM_OK;
+}
+
+}  // namespace ssmm
+
+extern "C" int ssmm_route_bucket(const float* logits, int T, int E, int topk, int n_shared, int renormalize,
+                                 int32_t* topk_ids, float* topk_w, int32_t* expert_offsets, int32_t* sel,
+                                 float* sel_w, int32_t* inv, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+  hipStream_t s = (hipStream_t)stream;
+  bool done = false;
+  const int st = check_route_bucket(logits, T, E, topk, n_shared, topk_ids, topk_w, expert_offsets, sel, sel_w, inv, s, &done);
+  if (st || done) return st;
+  if (!workspace) return SSMM_EINVAL;
+  if (workspace_bytes < ssmm_route_workspace_bytes(T, E, topk, n_shared)) return SSMM_EWORKSPACE;
+  return launch_route_bucket(logits, T, E, topk, n_shared, renormalize, topk_ids, topk_w, expert_offsets, sel, sel_w, inv,
+                             (int32_t*)workspace, s);
+}
+
+extern "C" int ssmm_route_bucket_noalloc(const float* logits, int T, int E, int topk, int n_shared, int renormalize,
+                                         int32_t* topk_ids, float* topk_w, int32_t* expert_offsets, int32_t* sel,
+                                         float* sel_w, int32_t* inv, void* stream) {
+  hipStream_t s = (hipStream_t)stream;
+  // the size limit first: it holds whatever else is wrong with the call
+  if (T > 0 && E > 0 && ((int64_t)T + kChunk - 1) / kChunk * E > kStaticCells) return SSMM_ELIMIT;
+  bool done = false;
+  int st = check_route_bucket(logits, T, E, topk, n_shared, topk_ids, topk_w, expert_offsets, sel, sel_w, inv, s, &done);
+  if (st || done) return st;
+  int32_t* counts = nullptr;
+  st = scratch_of_current_device(&counts);
+  if (st) return st;
+  // nothing in the array has to start at zero: histogram_kernel writes every cell scan_kernel reads
+  return launch_route_bucket(logits, T, E, topk, n_shared, renormalize, topk_ids, topk_w, expert_offsets, sel, sel_w, inv,
+                             counts, s);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported_and_bound():
 
 def test_strerror():
     assert B.strerror(0) == "ok"
-    for code in (B.SSMM_EINVAL, B.SSMM_ESHAPE, B.SSMM_EWORKSPACE, B.SSMM_EHIP, -99):
+    for code in (B.SSMM_EINVAL, B.SSMM_ESHAPE, B.SSMM_EWORKSPACE, B.SSMM_EHIP, B.SSMM_ELIMIT, -99):
         assert isinstance(B.strerror(code), str) and B.strerror(code)
 
 
