@@ -3,9 +3,11 @@
 
 A step = one pass of the whole hot path over one batch: route + bucket + SSMM gate/up
 (+SiLU*up) + SSMM down (+routing weight) + combine, inputs and encoded weights already
-resident in HBM.  Workload: the Mixtral-shaped layer (hidden 4096, FFN 14336, 8 experts,
-top-2, 2:4 weights) at 4096 tokens; the 16- and 256-token points of the same layer are
-reported in "sweep".  Prints ONE JSON line.
+resident in HBM.  Headline workload: the Mixtral-shaped layer (hidden 4096, FFN 14336, 8 experts,
+top-2, 2:4 weights) at 4096 tokens; its 16- and 256-token points are reported in "sweep", the
+other layer shapes of the benchmark set (tiny, Qwen-MoE-shaped, DeepSeek-MoE-shaped, the 75 %
+sparse variant at 4096 and 16 tokens) in "configs", each timed the same way with a roofline
+object for its first product and one for its down projection.  Prints ONE JSON line.
 """
 import argparse
 import json
@@ -21,12 +23,24 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
 
 
+def bytes_per_weight(fmt):
+    """Encoded bytes per dense weight element: 2:4 keeps half the values (1 B) plus 2 bits each (1/8 B);
+    an (N,M,V) level keeps N/M of that, plus its kernel-ready Sub-Row section ((1,2,V): 2 bits per lane
+    and k block = 1/32 B per dense element of the stored half; gathered: one byte per dense row and k block)."""
+    N, M, V = fmt
+    if N == M:
+        return 1.125
+    if N == 1 and M == 2:
+        return 0.5625 + 1.0 / 32
+    return 1.125 * N / M + 1.0 / 32
+
+
 def algorithmic_bytes(cfg, active_experts):
     """Bytes the method itself must move per layer pass: encoded weights of the experts that
     have tokens (1 B of values + 1/8 B of metadata per dense element for 2:4), each token row
     once per pair, h written and read once, yp written and read once, y written."""
     H, F, P, T = cfg.H, cfg.F, cfg.pairs, cfg.T
-    per_w = 1.125 if cfg.fmt == (1, 1, 0) else 0.59375   # (1,2,8): 0.5 values + 1/16 metadata + 1/32 source-row bits
+    per_w = bytes_per_weight(cfg.fmt)
     weights = 3 * H * F * per_w * active_experts
     acts = P * (2 * H + 4 * F + 4 * H) + 2 * T * H
     return weights, acts
@@ -35,17 +49,17 @@ def algorithmic_bytes(cfg, active_experts):
 def kernel_bytes(cfg, active_experts):
     """Algorithmic bytes of each kernel of the path (gate/up, down, combine)."""
     H, F, P, T = cfg.H, cfg.F, cfg.pairs, cfg.T
-    per_w = 1.125 if cfg.fmt == (1, 1, 0) else 0.59375
+    per_w = bytes_per_weight(cfg.fmt)
     gu = 2 * H * F * per_w * active_experts + P * (2 * H + 2 * F)
     dn = H * F * per_w * active_experts + P * (2 * F + 2 * H)
     cb = P * 2 * H + 2 * T * H
     return gu, dn, cb
 
 
-def measured_traffic(kernel, tokens=4096):
+def measured_traffic(kernel, tokens=4096, config="mixtral"):
     """HBM-side bytes per launch from the committed counter summary (collected with rocprofv3
-    --pmc in separate runs of this script; None if there is no summary for this token count)."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_ssmm_mixtral_T{tokens}.txt")
+    --pmc in separate runs of this script; None if there is no summary for this layer and token count)."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_ssmm_{config}_T{tokens}.txt")
     try:
         for line in open(path):
             if line.startswith(kernel + "_traffic_bytes_per_launch:"):
@@ -56,12 +70,19 @@ def measured_traffic(kernel, tokens=4096):
 
 
 def sustained_mfma_share():
-    """Share of the published sparse MFMA peak that back-to-back MFMAs on random bf16 operands
-    sustain on this chip (committed table of `bench.py --mfma-probe`; None if absent)."""
+    """Share of the published sparse MFMA peak that back-to-back v_smfmac_f32_32x32x32_bf16 on random bf16
+    operands sustain on this chip (committed table of `bench.py --mfma-probe`; None if absent)."""
     path = os.path.join(ROOT, "profiles", "sparse_mfma_rate_by_operand_bits.txt")
     try:
-        vals = [float(line.split("|")[5]) for line in open(path)
-                if line.startswith("random") and line.split("|")[1].strip() == "0"]
+        vals = []
+        for line in open(path):
+            c = [v.strip() for v in line.split("|")]
+            if line.startswith("#") or len(c) < 6:
+                continue
+            if len(c) == 7 and c[0].startswith("v_smfmac_f32_32x32x32") and c[1].startswith("random") and c[2] == "0":
+                vals.append(float(c[6]))
+            elif len(c) == 6 and c[0].startswith("random") and c[1] == "0":   # table without the instruction column
+                vals.append(float(c[5]))
         return sum(vals) / len(vals) if vals else None
     except (OSError, ValueError, IndexError):
         return None
@@ -154,51 +175,86 @@ def cpu_baseline(cfg, dense, point, torch, synth, max_pairs=512, repeats=16):
             "gpu_vs_oracle_rel_fro_on_sample": rel}
 
 
-def mfma_probe(torch, B, out_path=None):
-    """What the matrix pipes sustain for the SSMM kernels' instruction (v_smfmac_f32_32x32x32_bf16,
-    back to back, one wavefront per SIMD), by operand bits and idle issue slots: the chip is
-    power-limited under matrix load, so the published peak (clock 2.4 GHz) is not what a kernel
-    multiplying real data can reach.  Returns rows; dense-equivalent FLOPs per MFMA = 2 * 32^3."""
-    nbytes = int(B.lib().ssmm_probe_operand_bytes())
+PROBE_KINDS = [   # (constant of mfma_probe.h, instruction, dense-equivalent FLOPs per instruction, published peak TFLOP/s)
+    (0, "v_smfmac_f32_32x32x32_bf16", 2 * 32 * 32 * 32, 5000.0),
+    (1, "v_smfmac_f32_16x16x64_bf16", 2 * 16 * 16 * 64, 5000.0),
+    (2, "v_mfma_f32_32x32x16_bf16 (dense)", 2 * 32 * 32 * 16, 2500.0),
+]
+
+
+def probe_library():
+    """libssmm_probe.so (built by `python -m paper_2503_10725_amd.build`): bench-only, not part of the library."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2503_10725_amd", "libssmm_probe.so")
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: run `python -m paper_2503_10725_amd.build` first")
+    lib = ctypes.CDLL(path)
+    lib.ssmm_probe_operand_bytes.restype = ctypes.c_size_t
+    lib.ssmm_probe_mfma.restype = ctypes.c_int
+    lib.ssmm_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                    ctypes.c_void_p, ctypes.POINTER(ctypes.c_float), ctypes.c_void_p]
+    return lib
+
+
+def mfma_probe(torch, out_path=None):
+    """What the matrix pipes sustain, back to back, one wavefront per SIMD: the SSMM kernels' instruction
+    (v_smfmac_f32_32x32x32_bf16) by operand bits and idle issue slots -- the chip is power-limited under
+    matrix load, so the published peak (clock 2.4 GHz) is not what a kernel multiplying real data can
+    reach -- and, on the same random operands, the other sparse shape and the dense MFMA a kernel working
+    on expanded tiles would issue (the A/B the instruction choice rests on).  Returns rows."""
+    import ctypes
+    lib = probe_library()
+    nbytes = int(lib.ssmm_probe_operand_bytes())
     g = torch.Generator(device="cuda").manual_seed(7)
-    operands = {
-        "zeros": torch.zeros((nbytes,), dtype=torch.uint8, device="cuda"),
-        "ones (bf16 1.0, index bits 0x4 per group)": None,
-        "random (bf16 N(0,1), random index bits)": None,
-    }
     n_ab = 8 * 64 * 48
     one = torch.full((n_ab // 2,), 1.0, dtype=torch.bfloat16, device="cuda").view(torch.uint8)
     ix1 = torch.full((8 * 64,), 0x44444444, dtype=torch.int32, device="cuda").view(torch.uint8)
-    operands["ones (bf16 1.0, index bits 0x4 per group)"] = torch.cat([one, ix1])
     rnd = torch.randn((n_ab // 2,), generator=g, device="cuda").to(torch.bfloat16).view(torch.uint8)
     ixr = torch.randint(0, 256, (8 * 64 * 4,), generator=g, device="cuda", dtype=torch.uint8)
-    operands["random (bf16 N(0,1), random index bits)"] = torch.cat([rnd, ixr])
+    operands = {
+        "zeros": torch.zeros((nbytes,), dtype=torch.uint8, device="cuda"),
+        "ones (bf16 1.0, index bits 0x4 per group)": torch.cat([one, ix1]),
+        "random (bf16 N(0,1), random index bits)": torch.cat([rnd, ixr]),
+    }
+    sink = torch.zeros((1,), dtype=torch.float32, device="cuda")
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def run(buf, iters, idle, kind):
+        ms = ctypes.c_float(0.0)
+        st = lib.ssmm_probe_mfma(ctypes.c_void_p(buf.data_ptr()), buf.numel(), iters, idle, kind,
+                                 ctypes.c_void_p(sink.data_ptr()), ctypes.byref(ms), stream)
+        if st != 0:
+            raise RuntimeError(f"ssmm_probe_mfma: status {st}")
+        return ms.value
+
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     iters = 12000
     rows = []
+    rand = operands["random (bf16 N(0,1), random index bits)"]
     for _ in range(6):                       # ~30 ms of the heaviest load first: a cold chip runs faster for a while
-        B.probe_mfma(operands["random (bf16 N(0,1), random index bits)"], iters, 0)
+        run(rand, iters, 0, 0)
     for rep in range(2):
-        for name, buf in operands.items():
-            for idle in (0, -4, 1, 2, 4):      # -4: no idle slots, four consecutive MFMAs share their B operand
-                if idle and not name.startswith("random"):
-                    continue
-                ms = B.probe_mfma(buf, iters, idle)
-                ns = ms * 1e6 / (iters * 8)
-                rows.append({"operands": name, "s_nop7_per_mfma": idle, "repeat": rep, "ns_per_mfma": ns,
-                             "tflops_dense_equiv": cus * 4 * 2 * 32 ** 3 / ns * 1e-3})
+        for kind, instr, flops, peak in PROBE_KINDS:
+            for name, buf in operands.items():
+                for idle in (0, -4, 1, 2, 4):      # -4: no idle slots, four consecutive MFMAs share their B operand
+                    if idle and (kind != 0 or not name.startswith("random")):
+                        continue
+                    ns = run(buf, iters, idle, kind) * 1e6 / (iters * 8)
+                    tf = cus * 4 * flops / ns * 1e-3
+                    rows.append({"instruction": instr, "operands": name, "s_nop7_per_mfma": idle, "repeat": rep,
+                                 "ns_per_mfma": ns, "tflops_dense_equiv": tf, "share_of_published_peak": tf / peak})
     if out_path:
         with open(out_path, "w") as f:
-            f.write("# back-to-back v_smfmac_f32_32x32x32_bf16, one wavefront per SIMD, %d CUs, one MI355X\n" % cus)
+            f.write("# back-to-back matrix instructions, one wavefront per SIMD, %d CUs, one MI355X\n" % cus)
             f.write("# command: python3 bench.py --mfma-probe <this file>\n")
-            f.write("# published sparse bf16 peak: 5000 TFLOP/s dense-equivalent = 32 cycles per MFMA at 2.4 GHz = 13.3 ns\n")
+            f.write("# published peaks: sparse bf16 5000 TFLOP/s dense-equivalent (32 cycles per 32x32x32, 16 per 16x16x64, at 2.4 GHz = 13.3 / 6.7 ns); dense bf16 2500 TFLOP/s (32 cycles per 32x32x16)\n")
             f.write("# s_nop 7 = 8 wait states = 32 cycles of the wave's issue; the first one behind an MFMA hides under the MFMA's own 32 cycles\n")
-            f.write("# -4 in the second column: no idle slots, four consecutive MFMAs share their B operand (the order of the SSMM kernels)\n")
-            f.write("# operands | s_nop 7 behind each MFMA | repeat | ns per MFMA | dense-equiv TFLOP/s | share of the published peak\n")
+            f.write("# -4 in the third column: no idle slots, four consecutive MFMAs share their B operand (the order of the SSMM kernels)\n")
+            f.write("# instruction | operands | s_nop 7 behind each MFMA | repeat | ns per MFMA | dense-equiv TFLOP/s | share of its published peak\n")
             for r in rows:
-                f.write("%-44s | %2d | %d | %6.2f | %7.1f | %.3f\n" % (r["operands"], r["s_nop7_per_mfma"], r["repeat"],
-                                                                      r["ns_per_mfma"], r["tflops_dense_equiv"],
-                                                                      r["tflops_dense_equiv"] / 5000.0))
+                f.write("%-34s | %-44s | %2d | %d | %6.2f | %7.1f | %.3f\n" % (
+                    r["instruction"], r["operands"], r["s_nop7_per_mfma"], r["repeat"], r["ns_per_mfma"],
+                    r["tflops_dense_equiv"], r["share_of_published_peak"]))
     return rows
 
 
@@ -252,24 +308,64 @@ def ssmm_grid(torch, B, out_path=None):
     return rows_out
 
 
+def kernel_rooflines(cfg, pt, config_name):
+    """Roofline objects of the two SSMM kernels of a measured point: each is read against the roof that
+    bounds it at this shape -- the larger of its ideal times at the published peaks (dense bf16 MFMA on
+    the FLOPs it executes on the kept half of the weights; HBM on its algorithmic bytes) -- and carries
+    the other view beside it."""
+    gu_b, dn_b, cb_b = kernel_bytes(cfg, pt["active_experts"])
+    out = {}
+    for key, ms, nbytes, flops, what in (
+            ("roofline", pt["kernel_ms"]["gate_up"], gu_b, 2.0 * cfg.H * cfg.F * cfg.pairs, "gate/up"),
+            ("roofline_down", pt["kernel_ms"]["down"], dn_b, 1.0 * cfg.H * cfg.F * cfg.pairs, "down")):
+        t = ms * 1e-3
+        tf, gbs = flops / t / 1e12, nbytes / t / 1e9
+        mfma_bound = flops / (MFMA_BF16_PEAK_TFLOPS * 1e12) >= nbytes / (HBM_PEAK_GBS * 1e9)
+        r = {"kernel": f"SSMM {what} (v_smfmac_f32_32x32x32_bf16)", "bound": "mfma" if mfma_bound else "hbm",
+             "achieved": tf if mfma_bound else gbs, "peak": MFMA_BF16_PEAK_TFLOPS if mfma_bound else HBM_PEAK_GBS,
+             "unit": "TFLOP/s" if mfma_bound else "GB/s",
+             "frac": tf / MFMA_BF16_PEAK_TFLOPS if mfma_bound else gbs / HBM_PEAK_GBS,
+             "avg_launch_ms": ms, "executed_TFLOPs": tf, "frac_mfma": tf / MFMA_BF16_PEAK_TFLOPS,
+             "algorithmic_GBs": gbs, "frac_hbm": gbs / HBM_PEAK_GBS,
+             "traffic": measured_traffic("gate_up" if key == "roofline" else "down", cfg.T, config_name)}
+        out[key] = r
+    out["combine_GBs"] = cb_b / (pt["kernel_ms"]["combine"] * 1e-3) / 1e9
+    return out
+
+
+def public(pt):
+    return {k: v for k, v in pt.items() if k not in ("x", "logits", "y", "route")}
+
+
+WORKLOADS = {
+    "tiny": "tiny MoE layer: 128 tokens, hidden 512, FFN 1024, 8 experts top-2, 2:4 weights, N(0,1) router logits",
+    "mixtral": "Mixtral-shaped MoE layer: hidden 4096, FFN 14336, 8 experts top-2, 2:4 weights N(0,0.02), {T} tokens, uniform router logits",
+    "qwen": "Qwen-MoE-shaped layer: hidden 3584, FFN 2560, 64 experts top-8, 2:4 weights, {T} tokens, per-expert logit bias N(0,1) (skewed loads)",
+    "deepseek": "DeepSeek-MoE-shaped layer: hidden 2048, FFN 1408, 64 routed experts top-6 + 2 shared, 2:4 weights, {T} tokens",
+    "mixtral75": "Mixtral shape at 75 % weight sparsity: (1,2,8) Sub-Rows by L2 norm stacked on 2:4, {T} tokens, top-2",
+}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--tokens", type=int, default=4096, help="token count of the headline point")
-    ap.add_argument("--config", default="mixtral", help="layer of synth.CONFIGS to time (default: the headline one)")
+    ap.add_argument("--tokens", type=int, default=None, help="token count of the headline point (default: the layer's own, 4096 for the headline layer)")
+    ap.add_argument("--config", default="mixtral", help="layer of synth.CONFIGS to time as the headline (default: the Mixtral-shaped one)")
     ap.add_argument("--format", default=None, metavar="N,M,V",
                     help="time the chosen layer shape with another weight format, e.g. 4,8,32 (1,1,0 = plain 2:4)")
     ap.add_argument("--pre-expand", action="store_true",
                     help="with a gathered --format: expand the weights once, before the timed region, to plain 2:4 operands "
                          "(ssmm_expand_tiled_weights) and run the layer on those")
-    ap.add_argument("--no-sweep", action="store_true", help="skip the 16- and 256-token points")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the 16- and 256-token points of the headline layer")
+    ap.add_argument("--no-configs", action="store_true", help="skip the other layer shapes of the benchmark set")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for the FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--mfma-probe", metavar="FILE", default=None,
-                    help="instead of the layer benchmark: time back-to-back sparse MFMAs by operand bits, write the table to FILE")
+                    help="instead of the layer benchmark: time back-to-back matrix instructions (the kernels' sparse MFMA by "
+                         "operand bits, the other sparse shape, the dense MFMA), write the table to FILE")
     ap.add_argument("--ssmm-grid", metavar="FILE", default=None,
                     help="instead of the layer benchmark: time the stand-alone SSMM over a shape grid, write the table to FILE")
     args = ap.parse_args()
@@ -286,27 +382,31 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     if args.mfma_probe:
-        rows = mfma_probe(torch, B, args.mfma_probe)
-        print(json.dumps({"metric": "sustained sparse MFMA rate by operand bits", "rows": rows}))
+        rows = mfma_probe(torch, args.mfma_probe)
+        print(json.dumps({"metric": "sustained matrix-instruction rate by instruction and operand bits", "rows": rows}))
         return
     if args.ssmm_grid:
         rows = ssmm_grid(torch, B, args.ssmm_grid)
         print(json.dumps({"metric": "stand-alone SSMM dense-equiv TFLOP/s over a shape grid", "rows": rows}))
         return
+    import dataclasses
     base = synth.CONFIGS[args.config]
     if args.format:
-        import dataclasses
         base = dataclasses.replace(base, fmt=tuple(int(v) for v in args.format.split(",")))
-    if args.config != "mixtral" or args.format:
-        args.no_sweep = True
-        if args.tokens == 4096:
-            args.tokens = base.T
-    dense = synth.make_weights(base, "cuda")
-    enc = [B.compress_weights(w, base.fmt, canonical=False, tiled=True)["tiled"] for w in dense]
-    torch.cuda.synchronize()
+    default_run = args.config == "mixtral" and not args.format and not args.pre_expand and args.tokens is None
+    if not default_run:
+        args.no_sweep = args.no_configs = True
+    tokens = args.tokens if args.tokens is not None else base.T
+
+    def encode(cfg):
+        dense = synth.make_weights(cfg, "cuda")
+        enc = [B.compress_weights(w, cfg.fmt, canonical=False, tiled=True)["tiled"] for w in dense]
+        torch.cuda.synchronize()
+        return dense, enc
+
+    dense, enc = encode(base)
     run_base = base                       # what the timed calls are given; `base` stays the pruning format (oracle leg)
     if args.pre_expand:
-        import dataclasses
         shapes = [(base.F, base.H), (base.F, base.H), (base.H, base.F)]
         enc = [B.expand_tiled_weights(t, base.E_total, r, k, base.fmt) for t, (r, k) in zip(enc, shapes)]
         run_base = dataclasses.replace(base, fmt=(1, 1, 0))
@@ -320,51 +420,56 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    head = run_point(run_base.with_tokens(args.tokens), enc, args.steps, args.warmup, B, synth, torch)
+    head = run_point(run_base.with_tokens(tokens), enc, args.steps, args.warmup, B, synth, torch)
+    cfg = base.with_tokens(tokens)
+    rl = kernel_rooflines(cfg, head, args.config if not args.format else "-")
+    roofline = rl["roofline"]
+    roofline["flops"] = "executed on the kept half of the weights (dense-equivalent = 2x)"
+    roofline["traffic_unit"] = "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated; profiles/)"
+    share = sustained_mfma_share()
+    if share and roofline["bound"] == "mfma":   # context, not the peak: what the matrix pipes sustain on random operands at this chip's power limit
+        roofline["sustained"] = {"share_of_peak": share, "frac_of_sustained": roofline["frac"] / share,
+                                 "source": "profiles/sparse_mfma_rate_by_operand_bits.txt (bench.py --mfma-probe)"}
+    roofline["combine_GBs"] = rl["combine_GBs"]
+
     sweep = []
     if not args.no_sweep:
         for T in (16, 256):
             pt = run_point(base.with_tokens(T), enc, args.steps, args.warmup, B, synth, torch)
-            sweep.append({k: v for k, v in pt.items() if k not in ("x", "logits", "y", "route")})
-
-    cfg = base.with_tokens(args.tokens)
-    gu_ms = head["kernel_ms"]["gate_up"]
-    executed_flops_gu = 2.0 * cfg.H * cfg.F * cfg.pairs      # multiply-adds on kept weights only, x2
-    roofline = {"kernel": "ssmm_kernel2<gate/up> (v_smfmac_f32_32x32x32_bf16; 256 features x 160 or 128 tokens per block)", "bound": "mfma",
-                "achieved": executed_flops_gu / (gu_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": executed_flops_gu / (gu_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                "flops": "executed on the kept half of the weights (dense-equivalent = 2x)",
-                "avg_launch_ms": gu_ms, "traffic": measured_traffic("gate_up") if (args.tokens == 4096 and args.config == "mixtral" and not args.format) else None,
-                "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated; profiles/)"}
-    share = sustained_mfma_share()
-    if share:   # context, not the peak: what the matrix pipes sustain on random operands at this chip's power limit
-        roofline["sustained"] = {"share_of_peak": share, "frac_of_sustained": roofline["frac"] / share,
-                                 "source": "profiles/sparse_mfma_rate_by_operand_bits.txt (bench.py --mfma-probe)"}
-    gu_b, dn_b, cb_b = kernel_bytes(cfg, head["active_experts"])
-    roofline["hbm_view"] = {"gate_up_GBs": gu_b / (gu_ms * 1e-3) / 1e9,
-                            "down_GBs": dn_b / (head["kernel_ms"]["down"] * 1e-3) / 1e9,
-                            "combine_GBs": cb_b / (head["kernel_ms"]["combine"] * 1e-3) / 1e9}
-    for pt in sweep:
-        c = base.with_tokens(pt["T"])
-        b = kernel_bytes(c, pt["active_experts"])
-        pt["roofline"] = {"kernel": "ssmm_kernel2<gate/up>", "bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBS,
-                          "achieved": b[0] / (pt["kernel_ms"]["gate_up"] * 1e-3) / 1e9,
-                          "frac": b[0] / (pt["kernel_ms"]["gate_up"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                          "down_GBs": b[1] / (pt["kernel_ms"]["down"] * 1e-3) / 1e9,
-                          "traffic": measured_traffic("gate_up", pt["T"])}
+            row = public(pt)
+            row.update(kernel_rooflines(base.with_tokens(T), pt, args.config))
+            sweep.append(row)
 
     cpu = None
     if not args.no_cpu:
         cpu = cpu_baseline(cfg, dense, head, torch, synth)
+    del dense
+
+    configs = []
+    if not args.no_configs:
+        del enc
+        torch.cuda.empty_cache()
+        for name, T in (("tiny", None), ("qwen", None), ("qwen", 64), ("deepseek", None), ("deepseek", 64),
+                        ("mixtral75", None), ("mixtral75", 16)):
+            c0 = synth.CONFIGS[name]
+            if not configs or configs[-1]["config"] != name:
+                d_, e_ = encode(c0)
+                del d_
+            c = c0.with_tokens(T if T is not None else c0.T)
+            pt = run_point(c, e_, args.steps, args.warmup, B, synth, torch)
+            row = {"config": name, "workload": WORKLOADS[name].format(T=c.T), "hidden": c.H, "ffn": c.F, "experts": c.E,
+                   "shared_experts": c.S, "topk": c.topk, "format": list(c.fmt)}
+            row.update(public(pt))
+            row.update(kernel_rooflines(c, pt, name))
+            configs.append(row)
+            torch.cuda.empty_cache()
 
     out = {
         "metric": "dense-equiv TFLOP/s per MoE layer (route+bucket+SSMM gate/up+SiLU+SSMM down+combine)",
         "value": head["tflops_dense_equiv"], "unit": "TFLOP/s (dense-equivalent)", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": (f"Mixtral-shaped MoE layer: hidden 4096, FFN 14336, 8 experts top-2, 2:4 weights "
-                                f"N(0,0.02), {args.tokens} tokens, uniform router logits") if args.config == "mixtral"
-                   else f"{args.config}-shaped MoE layer of synth.CONFIGS, {args.tokens} tokens", "tokens": args.tokens,
+        "config": {"workload": WORKLOADS[args.config].format(T=tokens), "tokens": tokens,
                    "hidden": cfg.H, "ffn": cfg.F, "experts": cfg.E, "topk": cfg.topk, "format": list(cfg.fmt),
                    "weights_resident_as": "plain 2:4 operands, expanded once from the pruning format" if args.pre_expand
                    else "the pruning format"},
@@ -373,7 +478,7 @@ def main():
         "mfma_frac_sparse_peak": head["mfma_frac_sparse_peak"],
         "mfma_frac_dense_peak": head["tflops_dense_equiv"] / MFMA_BF16_PEAK_TFLOPS,
         "hbm_GBs": head["hbm_GBs"], "hbm_frac": head["hbm_frac"],
-        "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep,
+        "roofline": roofline, "roofline_down": rl["roofline_down"], "cpu_baseline": cpu, "sweep": sweep, "configs": configs,
         "paper_context": "paper reports only speedups on an RTX 4070 Super (up to 1.99x kernel vs VENOM, "
                          "1.58x model-level); no absolute number for this metric",
     }

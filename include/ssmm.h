@@ -284,25 +284,6 @@ size_t ssmm_matmul_workspace_bytes(int64_t rows, int64_t K, int n, ssmm_format f
 int ssmm_matmul(const void* a_tiled, int64_t rows, int64_t K, ssmm_format f, const uint16_t* b, int64_t n_b,
                 const int32_t* sel, int n, uint16_t* c, void* workspace, size_t workspace_bytes, void* stream);
 
-/*
- * Measurement aid (no passage of the paper: it prices the roofline the SSMM kernels are
- * read against).  Times iters x 8 back-to-back v_smfmac_f32_32x32x32_bf16 per wavefront,
- * one wavefront per SIMD on every CU, after one untimed launch of the same length.
- *   operands  in   device, at least ssmm_probe_operand_bytes() bytes: the A operands
- *                  (8 sets x 64 lanes x 16 bytes), B operands (x 32 bytes) and index
- *                  registers (x 4 bytes) the MFMAs multiply -- their bits set the power
- *                  the matrix pipes draw and with it the clock the chip sustains
- *   idle_slots     0, 1, 2 or 4: s_nop 7 (8 wait states) behind every MFMA;
- *                  -4: none, and four consecutive MFMAs share their B operand (the
- *                  order of the SSMM kernels)
- *   sink      out  device, one float (never written in practice; keeps the sums alive)
- *   ms_out    out  host: duration of the timed launch in milliseconds
- * Synchronises the stream.  SSMM_EWORKSPACE if operand_bytes is too small.
- */
-size_t ssmm_probe_operand_bytes(void);
-int ssmm_probe_mfma(const void* operands, size_t operand_bytes, int iters, int idle_slots, float* sink,
-                    float* ms_out, void* stream);
-
 #ifdef __cplusplus
 }
 #endif

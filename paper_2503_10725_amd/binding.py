@@ -62,8 +62,6 @@ EXPORTS = {
     "ssmm_matmul_workspace_bytes": (c_size_t, [c_int64, c_int64, c_int, Format]),
     "ssmm_matmul": (c_int, [c_void_p, c_int64, c_int64, Format, c_void_p, c_int64, c_void_p, c_int, c_void_p, c_void_p,
                             c_size_t, c_void_p]),
-    "ssmm_probe_operand_bytes": (c_size_t, []),
-    "ssmm_probe_mfma": (c_int, [c_void_p, c_size_t, c_int, c_int, c_void_p, POINTER(ctypes.c_float), c_void_p]),
 }
 
 _lib = None
@@ -82,6 +80,32 @@ def lib():
             fn.restype, fn.argtypes = res, args
         _lib = handle
     return _lib
+
+
+TUNE_LIB_PATH = os.path.join(_PKG, "libssmm_tune.so")
+
+
+class tuning_library:
+    """Context manager: calls inside go to libssmm_tune.so, the build of the same sources whose tile and
+    split rules read override knobs (SSMM_DOWN_SPLITS, SSMM_PIPE, ...) from the environment.  For tests
+    that force a code path and for sweeps; the library itself has no such knobs."""
+
+    def __enter__(self):
+        global _lib
+        if not os.path.exists(TUNE_LIB_PATH):
+            raise RuntimeError(f"{TUNE_LIB_PATH} is missing: run `python -m paper_2503_10725_amd.build` first")
+        self.saved = lib()
+        handle = ctypes.CDLL(TUNE_LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+        return handle
+
+    def __exit__(self, *exc):
+        global _lib
+        _lib = self.saved
+        return False
 
 
 def strerror(status):
@@ -273,16 +297,6 @@ def matmul(a_tiled, rows, K, fmt, b, sel=None, n=None, c=None, workspace=None):
                              _ptr(sel, torch.int32) if sel is not None else None, n, _ptr(c, torch.bfloat16),
                              _ptr(workspace), workspace.numel(), _stream()), "ssmm_matmul")
     return c
-
-
-def probe_mfma(operands, iters, idle_slots=0):
-    """Milliseconds of iters x 8 back-to-back sparse MFMAs per wavefront (one per SIMD, every
-    CU) on the operand bits in `operands` (uint8 device tensor)."""
-    sink = torch.zeros((1,), dtype=torch.float32, device=operands.device)
-    ms = ctypes.c_float(0.0)
-    _check(lib().ssmm_probe_mfma(_ptr(operands), operands.numel() * operands.element_size(), int(iters), int(idle_slots),
-                                 _ptr(sink), ctypes.byref(ms), _stream()), "ssmm_probe_mfma")
-    return ms.value
 
 
 class HipEvents:

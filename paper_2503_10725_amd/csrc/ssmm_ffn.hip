@@ -32,6 +32,7 @@
 // global-memory instruction and wait placed by hand and resident blocks that walk the tile list.
 // In both the MFMAs are asm: NO kernel here may spill (the build checks it) -- the compiler
 // stores a spilled accumulator right behind the MFMA that defines it, before it is written.
+#include <climits>
 #include <cmath>
 #include <cstdlib>
 
@@ -43,10 +44,12 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(__bf16)))) __bf16 bf16x16;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-#ifndef SSMM_DIAG
-#define SSMM_DIAG 0   // build-time diagnostics: 1 no MFMA, 2 no A loads, 4 no token-tile loads, 8 every block reads the same A tiles, 16 every expert reads expert 0's weights, 32 no LDS reads, 128 no wait for A operands, 256 no wait for the token tile, 512 no barrier (timing only; results wrong, addresses unaffected), 32768 per-block wait times written to the buffer named by SSMM_DBG_PTR_GU / _DN (8 x grid x 8 bytes)
-#endif
 constexpr int kStageK = 64;   // reduction elements per pipeline stage (two MFMA k blocks)
+// Consecutive blocks of a launch go round-robin over the accelerator dies (XCDs) of the device, each with
+// an L2 of its own; the tile list is dealt to the blocks in this many contiguous shares so that the tiles
+// that share operands meet in one L2.  Eight is the MI355X's count; on a device with another count the
+// results are the same and only that locality is lost.
+constexpr int kXcdGroups = 8;
 
 struct SsmmArgs {
   const uint16_t* act;            // B rows: x [T][K] (gathered through sel) or h [P][K]
@@ -68,7 +71,6 @@ struct SsmmArgs {
   int gN, gM;                     // gathered formats: N and M; row_tiles then counts DENSE 32-row tiles
   int stored_tiles;               // gathered formats: 32-row tiles of the stored matrix of one expert
   int n_tiles_max;                // upper bound on token tiles over all experts
-  unsigned long long* dbg;        // diagnostic builds only: per block (wait A, wait B + barrier, whole loop) in clock ticks
   // split reduction (down projection of small buckets): block (.., split) multiplies stages
   // [split*kper, min(K/64, (split+1)*kper)) and writes unscaled fp32 partial sums
   int ksplit, kper;
@@ -239,7 +241,6 @@ struct SsmmTile {
   // its SIMD's MFMA pipe idle meanwhile).  The fences keep every task where the source puts it.
   template <int BUF>
   __device__ inline void issue_b_chunk(int i) {
-    if (SSMM_DIAG & 4) return;
     load16_to_lds(brow[i], lds_dst[i] + BUF * kStageBytes);
     brow[i] += kStageK;
   }
@@ -248,7 +249,6 @@ struct SsmmTile {
   // advancing and the last stage is simply read again into a set nobody uses.
   template <int SET>
   __device__ inline void issue_a_stream(int x, bool more) {
-    if (SSMM_DIAG & 2) return;
     pin_order();
     if (GEN) {
       // The source bytes of the NEXT stage are requested first: loads return in order, so waiting
@@ -348,9 +348,8 @@ struct SsmmTile {
       for (int x = 0; x < NA * NP; x++) mfma_guard(op[x], x == NA * NP - 1);
 #pragma unroll
     for (int n = 0; n < NT; n++) {
-      if (!(SSMM_DIAG & 1))
 #pragma unroll
-        for (int x = 0; x < NA * NP; x++) smfmac<0>(acc[x][n], op[x], bf[n], idx[SET][x / NP]);
+      for (int x = 0; x < NA * NP; x++) smfmac<0>(acc[x][n], op[x], bf[n], idx[SET][x / NP]);
       bf[n] = read_b(base, n, 1);
       if (n == 0) load_tasks<LSET, LBUF, 0>(more, tokens);
       if (n == 1) load_tasks<LSET, LBUF, 1>(more, tokens);
@@ -374,9 +373,8 @@ struct SsmmTile {
       for (int x = 0; x < NA * NP; x++) mfma_guard(op[x], x == NA * NP - 1);
 #pragma unroll
     for (int n = 0; n < NT; n++) {
-      if (!(SSMM_DIAG & 1))
 #pragma unroll
-        for (int x = 0; x < NA * NP; x++) smfmac<1>(acc[x][n], op[x], bf[n], GEN ? idx1[SET][x / NP] : idx[SET][x / NP]);
+      for (int x = 0; x < NA * NP; x++) smfmac<1>(acc[x][n], op[x], bf[n], GEN ? idx1[SET][x / NP] : idx[SET][x / NP]);
       if (n == 0) load_tasks<LSET, LBUF, NT + 0>(more, tokens);
       if (n == 1) load_tasks<LSET, LBUF, NT + 1>(more, tokens);
       if (n == 2) load_tasks<LSET, LBUF, NT + 2>(more, tokens);
@@ -420,8 +418,8 @@ __global__ void __launch_bounds__(64 * WM * WN) ssmm_kernel(const SsmmArgs p) {
   constexpr int NTH = Tile::NTH, NB = Tile::NB, NA = Tile::NA, CH = Tile::CH, NP = Tile::NP;
   __shared__ uint4 lds[Tile::DB * NB * 8];   // token-tile ring
 
-  // ---- block -> (expert, row tile, token tile).  Consecutive blocks go round-robin over the 8
-  // XCDs, so each XCD is given a contiguous range of the logical order "expert, then row tile,
+  // ---- block -> (expert, row tile, token tile).  Consecutive blocks go round-robin over the
+  // device's XCDs, so each XCD is given a contiguous range of the logical order "expert, then row tile,
   // then token tile": the blocks that run together on an XCD are then all token tiles of a few
   // neighbouring row tiles of one expert, so an A tile is pulled into that XCD's L2 once and
   // shared by all token tiles, and the expert's token tile is shared by the row tiles in flight.
@@ -431,9 +429,10 @@ __global__ void __launch_bounds__(64 * WM * WN) ssmm_kernel(const SsmmArgs p) {
   const int MTB = (p.row_tiles + MT * WM - 1) / (MT * WM) * (SPLITK ? p.ksplit : 1);
   int total = 0;
   for (int i = 0; i < p.E_total; i++) total += (bucket_offset(p, i + 1) - bucket_offset(p, i) + NB - 1) / NB * MTB;
-  const int per_xcd = (total + 7) / 8;
-  if ((int)(blockIdx.x / 8) >= per_xcd) return;   // uniform over the block
-  const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  constexpr int nx = kXcdGroups;
+  const int per_xcd = (total + nx - 1) / nx;
+  if ((int)(blockIdx.x / nx) >= per_xcd) return;   // uniform over the block
+  const int L = (blockIdx.x % nx) * per_xcd + blockIdx.x / nx;
   int e = -1, row0 = 0, nvalid = 0, mtb = 0, split = 0;
   {
     int before = 0;   // blocks of the experts before i
@@ -471,7 +470,7 @@ __global__ void __launch_bounds__(64 * WM * WN) ssmm_kernel(const SsmmArgs p) {
 #pragma unroll
   for (int i = 0; i < MT; i++) {
     tile_id[i] = (mtb * WM + wm) * MT + i;
-    const int64_t tt = (SSMM_DIAG & 8) ? i : (int64_t)((SSMM_DIAG & 16) ? 0 : e) * MTtot + min(tile_id[i], MTtot - 1);   // clamp: loads stay in bounds
+    const int64_t tt = (int64_t)e * MTtot + min(tile_id[i], MTtot - 1);   // clamp: loads stay in bounds
     // gathered formats: tt counts dense tiles; the stored Sub-Rows of dense tile d of an expert lie in its stored tile d*N/M
     const int64_t ts = GEN ? (int64_t)e * p.stored_tiles + (int64_t)min(tile_id[i], MTtot - 1) * p.gN / p.gM : tt;
     t.av[i] = (const char*)p.a0_vals + ts * KB * 1024 + (int64_t)ks0 * 2048;
@@ -641,12 +640,6 @@ __device__ inline void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 constexpr int cmin(int a, int b) { return a < b ? a : b; }
-// shader clock, read through the scalar cache (diagnostic builds only: the wait also drains LDS reads)
-__device__ inline unsigned long long clock_now() {
-  unsigned long long t;
-  asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t) : : "memory");
-  return t;
-}
 
 // DS: register sets of A operands = LDS buffers of the token tile = stages in flight + 1.
 template <bool GATEUP, bool VEC, int MT, int NT, int WM, int WN, int DS>
@@ -705,7 +698,6 @@ struct SsmmPipe {
   uint32_t vb[CH];           // per lane: offset of its 16-byte piece of each transfer from bbase
   uint32_t dma_w;            // wave-uniform LDS byte address of this wave's slot of transfer 0, buffer 0
   uint32_t rd[4];            // LDS byte offsets in a buffer: this lane's two 16-byte pieces of k block 0, then k block 1
-  unsigned long long t_wait_a, t_wait_b;   // diagnostic builds only
   bf16x8 a[DS][NA][2];
   uint32_t idx[DS][NA];
   uint32_t vx[DS][NA];
@@ -719,7 +711,7 @@ struct SsmmPipe {
     const int x = q / IPS, part = q % IPS;
     if (part == 0) vm_load16<0>(a[SET][x][0], va, av[x]);
     if (part == 1) vm_load16<1024>(a[SET][x][1], va, av[x]);
-    if (part == 2 && !(SSMM_DIAG & 4096)) vm_load4(idx[SET][x], vm, am[x]);
+    if (part == 2) vm_load4(idx[SET][x], vm, am[x]);
     if (VEC && part == 3) vm_load2(vx[SET][x], vxo, ax[x]);
     if (q == LA_N - 1) {
       sa = __builtin_amdgcn_readfirstlane(min(sa + 1, KS - 1));
@@ -747,7 +739,6 @@ struct SsmmPipe {
   template <int SLOT, int BUF>
   __device__ inline void read_b_half(const char* ldsb, int kb, int n, int half) {
     typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
-    if (SSMM_DIAG & 32) return;
     const uint4 v = *(const uint4*)(ldsb + rd[2 * kb + half] + (BUF * kStageBytes + n * 4096));
     u32x8 w = __builtin_bit_cast(u32x8, bf[SLOT]);
     if (half == 0) {
@@ -773,7 +764,6 @@ struct SsmmPipe {
   // MFMA costs as much issue time as it saves (measured: equal run times on all layer shapes).
   template <int ABID, int N>
   __device__ inline void multiply(f32x16& c, bf16x8 av_, bf16x16 bv_, uint32_t iv_) {
-    if (SSMM_DIAG & 1) return;
     if (N < NT_AGPR) smfmac<ABID>(c, av_, bv_, iv_);
     else smfmac_v<ABID>(c, av_, bv_, iv_);
   }
@@ -783,11 +773,8 @@ struct SsmmPipe {
     constexpr int LSET = (SET + DS - 1) % DS;   // register set and LDS buffer this step fetches into
     constexpr int NEXT = (SET + 1) % DS;
     if (GI == GBAR) {
-      unsigned long long tq = 0;
-      if (SSMM_DIAG & 32768) tq = clock_now();
-      if (!(SSMM_DIAG & 256)) wait_vm<CNT_B>();
-      if (!(SSMM_DIAG & 512)) block_barrier();
-      if (SSMM_DIAG & 32768) t_wait_b += clock_now() - tq;
+      wait_vm<CNT_B>();
+      block_barrier();
     }
 #pragma unroll
     for (int m = 0; m < NM; m++) {
@@ -798,14 +785,12 @@ struct SsmmPipe {
         if (GL < G) read_b_half<(SET * G + GL) % R, SET>(ldsb, GL / NT, GL % NT, m);
         else read_b_half<(SET * G + GL) % R, NEXT>(ldsb, (GL - G) / NT, (GL - G) % NT, m);
       }
-      if (!(SSMM_DIAG & 2))
 #pragma unroll
-        for (int i = 0; i < LA_N; i++)
-          if (slot_a(i) == GI * NM + m) issue_a_part<LSET>(i, KS);
-      if (!(SSMM_DIAG & 4))
+      for (int i = 0; i < LA_N; i++)
+        if (slot_a(i) == GI * NM + m) issue_a_part<LSET>(i, KS);
 #pragma unroll
-        for (int i = 0; i < CH; i++)
-          if (slot_b(i) == GI * NM + m) issue_b<LSET>(i, KS);
+      for (int i = 0; i < CH; i++)
+        if (slot_b(i) == GI * NM + m) issue_b<LSET>(i, KS);
     }
   }
   template <int SET, int GI>
@@ -816,10 +801,7 @@ struct SsmmPipe {
   // one pipeline step; KS = number of stages, SET = stage index % DS
   template <int SET>
   __device__ inline void step(int KS, const char* ldsb) {
-    unsigned long long tq = 0;
-    if (SSMM_DIAG & 32768) tq = clock_now();
-    if (!(SSMM_DIAG & 128)) wait_vm<CNT_A>();
-    if (SSMM_DIAG & 32768) t_wait_a += clock_now() - tq;
+    wait_vm<CNT_A>();
 #pragma unroll
     for (int x = 0; x < NA; x++) {   // everything below sees the registers as written here, after the wait
       asm volatile("" : "+v"(a[SET][x][0]), "+v"(a[SET][x][1]), "+v"(idx[SET][x]));
@@ -850,12 +832,10 @@ struct SsmmPipe {
   template <int V>
   __device__ inline void prologue(int KS) {
     constexpr int SET = V + DS - 1;
-    if (!(SSMM_DIAG & 2))
 #pragma unroll
-      for (int q = 0; q < LA_N; q++) issue_a_part<SET>(q, KS);
-    if (!(SSMM_DIAG & 4))
+    for (int q = 0; q < LA_N; q++) issue_a_part<SET>(q, KS);
 #pragma unroll
-      for (int i = 0; i < CH; i++) issue_b<SET>(i, KS);
+    for (int i = 0; i < CH; i++) issue_b<SET>(i, KS);
     if constexpr (V + 1 < 0) prologue<V + 1>(KS);
   }
   template <int U>
@@ -960,8 +940,6 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) ssmm_kernel2(const SsmmArgs
   __shared__ int32_t side_sel[CH * NTH];   // token row of every 16-byte slot this block stages, for the tile after the current one
   __shared__ float side_w[2][NBW * 64];    // routing weights of the tile's rows (two tiles alive: the one multiplied, the one before it)
   __shared__ int32_t tab_cum[kMaxBuckets + 1], tab_off[kMaxBuckets + 1];   // tiles in front of each bucket; bucket offsets
-  unsigned long long t_entry = 0, t_loops = 0;
-  if (SSMM_DIAG & 32768) t_entry = clock_now();
 
   // tile -> (expert, row tile, token tile): see ssmm_kernel.  The number of tiles is known only
   // here; each XCD gets an equal share of it.  Order inside an expert: row tile, then split of the
@@ -982,8 +960,9 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) ssmm_kernel2(const SsmmArgs
   }
   __syncthreads();
   const int total = __builtin_amdgcn_readfirstlane(tab_cum[p.E_total]);
-  const int per_xcd = (total + 7) / 8;
-  const int xcd = blockIdx.x % 8, nslots = gridDim.x / 8;
+  constexpr int nx = kXcdGroups;
+  const int per_xcd = (total + nx - 1) / nx;
+  const int xcd = blockIdx.x % nx, nslots = gridDim.x / nx;
   struct Where {
     int row0, nvalid, mtb, split, e;
   };
@@ -1043,7 +1022,6 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) ssmm_kernel2(const SsmmArgs
     t.rd[2] = rowb + (((4 + 2 * ph) ^ swz) << 4);
     t.rd[3] = rowb + (((5 + 2 * ph) ^ swz) << 4);
   }
-  if (SSMM_DIAG & 32768) t.t_wait_a = t.t_wait_b = 0;
 
   const uint32_t sel_w0 = __builtin_amdgcn_readfirstlane(lds_address(side_sel) + wv * 256);
   const uint32_t w_w0 = __builtin_amdgcn_readfirstlane(lds_address(side_w) + wv * 256);
@@ -1117,7 +1095,7 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) ssmm_kernel2(const SsmmArgs
     }
   };
 
-  int li = blockIdx.x / 8;
+  int li = blockIdx.x / nx;
   bool have_cur = locate(li, cur), have_prev = false;
   if (!have_cur) return;
   request_rows(cur, 1);
@@ -1127,6 +1105,10 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) ssmm_kernel2(const SsmmArgs
   for (;;) {
     // Order: aim the streams at the tile and request its first stages; epilogue of the tile
     // multiplied before (hides their latency); request the rows of the tile after; clear; multiply.
+    // Nothing is in flight here: the multiplication ended with every load landed.  Said once more
+    // for the build's check of the assembly, which follows every path through the loop without
+    // correlating its branches (the pass that only runs the last epilogue requests no stages).
+    wait_vm<0>();
     ln = lane_again();
     if (have_cur) {
       const int ks0 = SPLITK ? cur.split * p.kper : 0;                       // first stage of this tile
@@ -1135,9 +1117,7 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) ssmm_kernel2(const SsmmArgs
 #pragma unroll
       for (int i = 0; i < MT; i++) {
         const int tile = (cur.mtb * WM + wm) * MT + i;
-        const int64_t tt = (SSMM_DIAG & 8)      ? i
-                           : (SSMM_DIAG & 2048) ? wm * MT + i   // every block reads the first row tiles of expert 0: L2 resident
-                                                : (int64_t)cur.e * MTtot + min(tile, MTtot - 1);   // clamp: loads stay in bounds
+        const int64_t tt = (int64_t)cur.e * MTtot + min(tile, MTtot - 1);   // clamp: loads stay in bounds
         t.av[i] = (const char*)p.a0_vals + tt * KB * 1024 + (int64_t)ks0 * 2048;
         t.am[i] = (const char*)p.a0_meta + tt * (KB / 2) * 256 + (int64_t)ks0 * 256;
         if (VEC) t.ax[i] = (const char*)p.a0_vidx + tt * (KB / 2) * 128 + (int64_t)ks0 * 128;
@@ -1176,25 +1156,12 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) ssmm_kernel2(const SsmmArgs
     if (have_next) request_rows(next, parity ^ 1);
 
     t.clear();
-    unsigned long long t_begin = 0;
-    if (SSMM_DIAG & 32768) t_begin = clock_now();
     t.mainloop(KS, (const char*)lds);
-    if (SSMM_DIAG & 32768) t_loops += clock_now() - t_begin;
 
     prev = cur;
     have_prev = true;
     cur = next;
     have_cur = have_next;
-  }
-  if ((SSMM_DIAG & 32768) && p.dbg && tid == 0) {
-    unsigned long long* o = p.dbg + 8 * (size_t)blockIdx.x;
-    o[0] = t.t_wait_a;
-    o[1] = t.t_wait_b;
-    o[2] = t_loops;                 // waits + steps of all tiles of the block
-    o[3] = clock_now() - t_entry;   // whole block
-    o[4] = 0;
-    o[5] = t_entry;
-    o[6] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));   // HW_ID
   }
 }
 
@@ -1262,6 +1229,46 @@ __global__ void __launch_bounds__(256) combine_split_kernel(const float* __restr
 
 inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
+// Tuning overrides of the tile and split rules below.  The library as built for use has none: every
+// knob reads as unset and the rules alone decide, so what a call computes depends on its arguments
+// only.  A build with -DSSMM_TUNING (sweeps on the device, never the shipped library) reads them from
+// the environment at every call.
+constexpr int kUnset = INT32_MIN;
+inline int knob(const char* name) {
+#ifdef SSMM_TUNING
+  const char* v = getenv(name);
+  return v ? atoi(v) : kUnset;
+#else
+  (void)name;
+  return kUnset;
+#endif
+}
+
+// Compute units of the current device, asked for once per device.
+struct DeviceShape {
+  int cus;
+};
+inline int device_shape(DeviceShape* out) {
+  constexpr int kMaxDevices = 64;
+  static int known[kMaxDevices];   // 0: not asked yet
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SSMM_EHIP;
+  int cus = __atomic_load_n(&known[dev], __ATOMIC_ACQUIRE);
+  if (cus == 0) {
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) return SSMM_EHIP;
+    __atomic_store_n(&known[dev], cus, __ATOMIC_RELEASE);
+  }
+  out->cus = cus;
+  return SSMM_OK;
+}
+// Compute units the tile and split rules reckon with: those of the current device; where none is
+// visible (size queries on a host without a GPU) those of the MI355X.
+inline int compute_units() {
+  DeviceShape d;
+  return device_shape(&d) == SSMM_OK ? d.cus : 256;
+}
+
+
 // Tile shape by the mean bucket size: 2 = large buckets (MFMA-bound: 128/160-token tiles, 256 or
 // 512 rows per block), 1 = 128-token tiles with few rows per block (HBM-bound: the tile is wide
 // enough that most experts need one, so their weights are streamed once, and narrow in rows so
@@ -1283,7 +1290,7 @@ inline int down_splits(int shape, int64_t P, int H, int F, int E_total, ssmm_for
   const int64_t active = P < E_total ? P : E_total;                  // experts that can have tokens
   const int64_t tiles = (P / active + NB - 1) / NB;                  // token tiles of an average expert
   const int64_t blocks = (rc + rows_per_block - 1) / rows_per_block * active * tiles;
-  int S = (int)((256 + blocks / 2) / blocks);
+  int S = (int)((compute_units() + blocks / 2) / blocks);
   S = S < 1 ? 1 : S > 8 ? 8 : S;
   const int KS = F / kStageK;
   while (S > 1 && KS / S < 8) S--;
@@ -1306,8 +1313,8 @@ inline int64_t tall_down_blocks(int64_t P, int H, int E_total, ssmm_format f) {
 inline int tall_down_splits(int64_t P, int H, int F, int E_total, ssmm_format f) {
   if (tile_shape(P, E_total) != 2 || is_vectorwise(f) || gathered_format(f)) return 1;
   const int64_t blocks = tall_down_blocks(P, H, E_total, f);
-  if (blocks < 1 || blocks > 128) return 1;
-  int S = (int)(256 / blocks);
+  if (blocks < 1 || blocks > compute_units() / 2) return 1;
+  int S = (int)(compute_units() / blocks);
   S = S > 4 ? 4 : S;
   const int KS = F / kStageK;
   while (S > 1 && KS / S < 8) S--;
@@ -1317,33 +1324,41 @@ inline int tall_down_splits(int64_t P, int H, int F, int E_total, ssmm_format f)
 template <bool GATEUP, bool VEC, int MT, int NT, int WM, int WN, int DS, bool GEN = false, bool ANYACT = false, bool SPLITK = false>
 int launch_ssmm(SsmmArgs a, int64_t P, hipStream_t s) {
   constexpr int NB = 32 * NT * WN;
+  DeviceShape dev;
+  if (int st = device_shape(&dev)) return st;
   if (!SPLITK) a.ksplit = 1;
   a.pairs = P;
   const int MTB = (a.row_tiles + MT * WM - 1) / (MT * WM) * a.ksplit;
   a.n_tiles_max = (int)((P + NB - 1) / NB) + a.E_total;   // every expert adds at most one ragged tile
   int64_t grid = (int64_t)MTB * a.n_tiles_max;
-  grid = (grid + 7) / 8 * 8;
+  grid = (grid + kXcdGroups - 1) / kXcdGroups * kXcdGroups;
   auto kern = ssmm_kernel<GATEUP, VEC, MT, NT, WM, WN, DS, GEN, ANYACT, SPLITK>;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * WM * WN), 0, s, a);
   SSMM_RETURN_IF_LAUNCH_FAILED();
   return SSMM_OK;
 }
 
-// act_bytes: size of the token matrix the kernel gathers from (32-bit offsets inside the kernel)
+// Blocks a launch of the hand-scheduled kernels gets: one resident set (OCC per compute unit) when the
+// tile list may be longer than that, else one block per possible tile.
+inline int64_t resident_grid(int64_t tiles_bound, int occ, const DeviceShape& dev) {
+  int64_t grid = (tiles_bound + kXcdGroups - 1) / kXcdGroups * kXcdGroups;
+  const int64_t resident = (int64_t)dev.cus * occ / kXcdGroups * kXcdGroups;
+  const int persistent = knob("SSMM_PERSISTENT");   // 0: one block per tile
+  if (persistent != 0 && grid > resident) grid = resident;
+  return grid;
+}
+
 template <bool GATEUP, bool VEC, int MT, int NT, int WM, int WN, int DS, int OCC = 1, bool SPLITK = false, bool ANYACT = false>
 int launch_ssmm2(SsmmArgs a, int64_t P, hipStream_t s) {
   constexpr int NB = 32 * NT * WN;
+  DeviceShape dev;
+  if (int st = device_shape(&dev)) return st;
   if (!SPLITK) a.ksplit = 1;
   a.pairs = P;
   const int MTB = (a.row_tiles + MT * WM - 1) / (MT * WM) * a.ksplit;
   a.n_tiles_max = (int)((P + NB - 1) / NB) + a.E_total;   // every expert adds at most one ragged tile
-  int64_t grid = (int64_t)MTB * a.n_tiles_max;
-  grid = (grid + 7) / 8 * 8;
-  // one resident set of blocks walks the tile list (256 CUs, OCC blocks each: four waves = one per SIMD)
-  static const bool persistent = !(getenv("SSMM_PERSISTENT") && atoi(getenv("SSMM_PERSISTENT")) == 0);   // tuning knob
-  if (persistent && grid > 256 * OCC) grid = 256 * OCC;
-  if (SSMM_DIAG & 32768)
-    if (const char* ptr = getenv(GATEUP ? "SSMM_DBG_PTR_GU" : "SSMM_DBG_PTR_DN")) a.dbg = (unsigned long long*)strtoull(ptr, nullptr, 0);
+  const int64_t bound = (int64_t)MTB * a.n_tiles_max;
+  const int64_t grid = resident_grid(bound, OCC, dev);
   auto kern = ssmm_kernel2<GATEUP, VEC, MT, NT, WM, WN, DS, OCC, SPLITK, ANYACT>;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * WM * WN), 0, s, a);
   SSMM_RETURN_IF_LAUNCH_FAILED();
@@ -1402,7 +1417,139 @@ inline int launch_expand_gathered(const void* tiled, int E, int64_t rows, int64_
 // the layer expands gathered weights when its buckets are large: a mean of 256 pairs per expert and
 // more (measured on the Mixtral shape, (4,8,32): the pass costs what the gathering kernels lose at 900 tokens)
 inline bool expands_weights(ssmm_format f, int64_t P, int E_total) {
-  return gathered_format(f) && tile_shape(P, E_total) == 2 && P / E_total >= 256;
+  return gathered_format(f) && tile_shape(P, E_total) == 2 && P / E_total >= 256 && knob("SSMM_NO_EXPAND") == kUnset;
+}
+
+// What one call of the layer launches, decided on the host from its shapes alone (the bucket sizes
+// stay on the device, so the rules work with a bucket "somewhat above the mean").  The workspace
+// size and the call itself both read this plan, so they cannot disagree.
+enum DownKernel { kDownSmall, kDownMedium, kDownMedium5, kDownHalf, kDownTall };
+struct FfnPlan {
+  int64_t P;
+  bool expanded;         // gathered format multiplied as plain 2:4 operands expanded into the workspace
+  bool gen, vec;         // format class the kernels see: gathered / (1,2,V) masked / neither (plain 2:4)
+  int shape;             // tile class by mean bucket size (tile_shape), lowered for small gathered buckets
+  int gen_first_shape;   // gathered formats: tile class of the first product
+  int pipe, pipe_down;   // 2: hand-scheduled kernels, 1: compiler-scheduled ones
+  int gshape;            // first product on the hand-scheduled kernels: tile class
+  bool wide5;            //   ... and 160 instead of 128 tokens at the widest class
+  int down_kernel;       // DownKernel (hand-scheduled kernels, plain 2:4)
+  int splits, kper;      // slices of the down projection's reduction (1: whole sums), stages per slice
+  size_t yp_off, extra_off, bytes;   // workspace: h at 0, yp, partial sums / expanded weights
+};
+
+inline FfnPlan plan_ffn(int T, int H, int F, int E_total, int slots, ssmm_format f) {
+  FfnPlan pl = {};
+  const int64_t P = pl.P = (int64_t)T * slots;
+  pl.expanded = expands_weights(f, P, E_total);
+  const ssmm_format fk = pl.expanded ? ssmm_format{1, 1, 0} : f;   // what the kernels multiply
+  pl.gen = gathered_format(fk);
+  pl.vec = is_vectorwise(fk) && !pl.gen;
+  int shape = tile_shape(P, E_total);
+  if (const int want = knob("SSMM_TILE_SHAPE"); want >= 0 && want <= 2) shape = want;
+  pl.pipe = 2;
+  if (const int want = knob("SSMM_PIPE"); want != kUnset) pl.pipe = want;   // 1: compiler-scheduled loop
+  pl.pipe_down = pl.pipe;
+  // the hand-scheduled kernels address the token matrix with 32-bit offsets
+  if ((int64_t)T * H * 2 >= (int64_t)1 << 32) pl.pipe = 1;
+  // plain 2:4: h is read in consecutive rows and the offsets count from a tile's first row
+  if (P * F * 2 >= (int64_t)1 << 32 && (is_vectorwise(fk) || (int64_t)256 * F * 2 >= (int64_t)1 << 32)) pl.pipe_down = 1;
+  if (pl.gen) pl.pipe = pl.pipe_down = 1;
+  // Gathered formats, up to 64 pairs per expert: the down projection (reduction split, many blocks)
+  // is faster on 32-token tiles than on 64-token ones (measured); the first product only while one
+  // 32-token tile holds a bucket somewhat above the mean -- a second tile streams the weights again.
+  pl.gen_first_shape = shape;
+  if (pl.gen && shape == 1 && P / E_total <= 64) {
+    const double mean = (double)(P / E_total);
+    shape = 0;
+    pl.gen_first_shape = mean + 2.0 * sqrt(mean) <= 32.0 ? 0 : 1;
+  }
+  pl.shape = shape;
+  const int64_t active = P < E_total ? (P > 0 ? P : 1) : E_total;   // experts that can have tokens
+  const double est = (double)(P / active) + 2.0 * sqrt((double)(P / active));   // a bucket somewhat above the mean
+
+  // ---- first product on the hand-scheduled kernels.  The widest tile (256 output features x 128
+  // tokens per block) also wins for small buckets, as long as it gives every CU a block: the weights
+  // stream once per expert whatever the tile, and the wide tile needs half the blocks and transfers
+  // per byte (measured on the Mixtral shape from 8 to 512 tokens: equal at 16 tokens, 8 % faster at
+  // 256, 21 % at 512).  (1,2,V): the narrow tiles stay ahead below 20 pairs per expert (measured);
+  // F = 1408: half a tile of overhang costs what the wide tile gains.
+  pl.gshape = shape;
+  {
+    const int64_t wide_blocks = (F + 255) / 256 * active * ((P / active + 127) / 128);
+    const int64_t wide_rows = (F + 255) / 256 * 256;   // rows the wide tiles stream (the last tile may hang over)
+    if (!pl.vec && wide_blocks >= compute_units() * 25 / 32 && (wide_rows - F) * 32 <= F) pl.gshape = 2;   // 200 blocks on 256 CUs
+    if (const int want = knob("SSMM_GU_SHAPE"); want >= 0 && want <= 2) pl.gshape = want;
+    // 128- or 160-token tiles for the wide shape: the 160-token tile reuses every weight operand
+    // five times instead of four (measured 3-11 % faster per token from 512 to 8192 tokens on the
+    // Mixtral shape) but pads more; it is taken when a bucket of mean + 2 sqrt(mean) pairs pads to
+    // at most 10 % more tokens with it.
+    const double pad4 = ceil(est / 128.0) * 128.0, pad5 = ceil(est / 160.0) * 160.0;
+    pl.wide5 = pad5 <= 1.1 * pad4;
+    if (const int want = knob("SSMM_GU_NT5"); want != kUnset) pl.wide5 = want == 1;
+  }
+
+  // ---- down projection
+  const int KS = F / kStageK;
+  int splits = 1;
+  pl.down_kernel = shape == 2 ? kDownTall : shape == 1 ? kDownMedium : kDownSmall;
+  if (pl.pipe_down != 1) {
+    auto forced_splits = [&](int v) {   // tuning knob: 1..8, small and medium buckets only
+      const int want = knob("SSMM_DOWN_SPLITS");
+      return want >= 1 && want <= 8 && shape < 2 ? want : v;
+    };
+    splits = forced_splits(down_splits(shape, P, H, F, E_total, fk));
+    if (!pl.vec) {
+      int dshape = shape;
+      if (knob("SSMM_DOWN_SHAPE") == 1 && shape == 2) dshape = 1;   // the medium tile (unsplit) where the large one was chosen
+      // large buckets, but so few of them that 512-row tiles would leave CUs without a block: half-height
+      // tiles (measured on the Mixtral shape: 5-6 % at 768 and 1024 tokens) ...
+      bool half_height = dshape == 2 && tall_down_blocks(P, H, E_total, fk) <= compute_units() * 5 / 8;   // 160 blocks on 256 CUs
+      if (const int want = knob("SSMM_DOWN_HALF"); want != kUnset) half_height = dshape == 2 && want == 1;
+      // ... or, with fewer still, the tall tile with its reduction in 2 to 4 slices
+      int tall_splits = dshape == 2 && !pl.expanded ? tall_down_splits(P, H, F, E_total, fk) : 1;
+      if (knob("SSMM_DOWN_TALLSPLIT") == 0) tall_splits = 1;
+      // medium buckets that one 160-token tile holds but a 128-token tile does not (a second,
+      // nearly empty tile would stream the expert's weights again)
+      bool medium5 = dshape == 1 && ceil(est / 160.0) < ceil(est / 128.0);
+      if (const int want = knob("SSMM_DOWN_NT5"); want != kUnset) medium5 = dshape == 1 && want == 1;
+      if (medium5) {
+        pl.down_kernel = kDownMedium5;
+        splits = forced_splits(down_splits(shape, P, H, F, E_total, fk, 160));
+      } else if (tall_splits > 1) {
+        pl.down_kernel = kDownTall;
+        splits = tall_splits;
+      } else if (half_height) {
+        pl.down_kernel = kDownHalf;
+        splits = 1;
+      } else {
+        pl.down_kernel = dshape == 2 ? kDownTall : dshape == 1 ? kDownMedium : kDownSmall;
+        if (dshape == 2) splits = 1;
+      }
+    } else if (shape == 2) {
+      splits = 1;
+    }
+  } else if (pl.gen && shape < 2 && P * F * 2 < (int64_t)1 << 32) {
+    // small buckets: few rows per block and the reduction split, so that every CU has blocks to
+    // stream weights with (the partial sums go the way of the hand-scheduled kernels' split)
+    const int rows_per_block = shape == 1 ? 256 : 128, NBg = shape == 1 ? 64 : 32;
+    const int64_t blocks = (H + rows_per_block - 1) / rows_per_block * active * ((P / active + NBg - 1) / NBg);
+    splits = (int)((4 * compute_units() + blocks / 2) / blocks);   // measured on the Mixtral shape at 16 and 256 tokens: four and two splits
+    splits = splits < 1 ? 1 : splits > 8 ? 8 : splits;
+    if (const int want = knob("SSMM_DOWN_SPLITS"); want >= 1 && want <= 8) splits = want;
+    while (splits > 1 && KS / splits < 8) splits--;
+  }
+  pl.kper = (KS + splits - 1) / splits;
+  pl.splits = (KS + pl.kper - 1) / pl.kper;   // no empty slice
+
+  // ---- workspace: h [P][F] bf16, yp [P][H] bf16, then the fp32 partial sums of a split down projection
+  // or (gathered formats with large buckets) the three weight tensors in plain 2:4 operand order
+  const size_t part = pl.splits > 1 ? align256((size_t)pl.splits * P * H * 4) : 0;
+  const size_t expanded = pl.expanded ? 2 * plain_tiled_bytes(E_total, F, H) + plain_tiled_bytes(E_total, H, F) : 0;
+  pl.yp_off = align256((size_t)P * F * 2);
+  pl.extra_off = pl.yp_off + align256((size_t)P * H * 2);
+  pl.bytes = pl.extra_off + (part > expanded ? part : expanded) + 256;
+  return pl;
 }
 
 }  // namespace ssmm
@@ -1411,15 +1558,7 @@ using namespace ssmm;
 
 extern "C" size_t ssmm_ffn_workspace_bytes(int T, int H, int F, int E_total, int slots, ssmm_format f) {
   if (T < 0 || H < 1 || F < 1 || slots < 1 || E_total < 1) return 0;
-  const size_t P = (size_t)T * slots;
-  // h [P][F] bf16, yp [P][H] bf16, and for small buckets the fp32 partial sums of the split down projection
-  const size_t part = tile_shape((int64_t)P, E_total) < 2            ? align256(8 * P * H * 4)
-                      : tall_down_splits((int64_t)P, H, F, E_total, f) > 1
-                          ? align256((size_t)tall_down_splits((int64_t)P, H, F, E_total, f) * P * H * 4)
-                          : 0;
-  // gathered formats with large buckets: the three weight tensors in plain 2:4 operand order
-  const size_t expanded = expands_weights(f, (int64_t)P, E_total) ? 2 * plain_tiled_bytes(E_total, F, H) + plain_tiled_bytes(E_total, H, F) : 0;
-  return align256(P * F * 2) + align256(P * H * 2) + part + expanded + 256;
+  return plan_ffn(T, H, F, E_total, slots, f).bytes;
 }
 
 extern "C" int ssmm_expand_tiled_weights(const void* tiled, int E, int64_t rows, int64_t K, ssmm_format f, void* tiled_plain,
@@ -1462,17 +1601,17 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
   if (T == 0) return SSMM_OK;
   if (!x || !wg_tiled || !wu_tiled || !wd_tiled || !expert_offsets || !sel || !sel_w || !inv || !y || !workspace)
     return SSMM_EINVAL;
-  if (workspace_bytes < ssmm_ffn_workspace_bytes(T, H, F, E_total, slots, f)) return SSMM_EWORKSPACE;
+  const FfnPlan pl = plan_ffn(T, H, F, E_total, slots, f);
+  if (workspace_bytes < pl.bytes) return SSMM_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   auto mark = [&](int i) { return events ? hipEventRecord((hipEvent_t)events[i], s) == hipSuccess : true; };
-  const int64_t P = (int64_t)T * slots;
-  uint16_t* h = (uint16_t*)workspace;
-  uint16_t* yp = (uint16_t*)((char*)workspace + align256((size_t)P * F * 2));
+  const int64_t P = pl.P;
+  char* const ws = (char*)workspace;
+  uint16_t* h = (uint16_t*)ws;
+  uint16_t* yp = (uint16_t*)(ws + pl.yp_off);
 
-  bool expanded = expands_weights(f, P, E_total);   // their space in the workspace is where the partial sums of a split go otherwise
-  if (getenv("SSMM_NO_EXPAND")) expanded = false;   // tuning knob: gathering kernels at every bucket size
-  if (expanded) {   // gathered format, large buckets: multiply in plain 2:4 operand order
-    char* xb = (char*)workspace + align256((size_t)P * F * 2) + align256((size_t)P * H * 2);
+  if (pl.expanded) {   // gathered format, large buckets: multiply in plain 2:4 operand order
+    char* xb = ws + pl.extra_off;
     const size_t szg = plain_tiled_bytes(E_total, F, H);
     st = launch_expand_gathered(wg_tiled, E_total, F, H, f, xb, s);
     if (st) return st;
@@ -1489,8 +1628,8 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
     f.V = 0;
   }
   // sections of a kernel-ready weight buffer: values, index words, (vector-wise only) source-row bits
-  const bool gen = gathered_format(f);          // operands gathered lane by lane (compiler-scheduled kernels)
-  const bool vec = is_vectorwise(f) && !gen;    // (1,2,V): operands multiplied twice, masked
+  const bool gen = pl.gen;   // operands gathered lane by lane (compiler-scheduled kernels)
+  const bool vec = pl.vec;   // (1,2,V): operands multiplied twice, masked
   auto bind = [&](const void* tiled, int64_t w_rows, int64_t w_K, const bf16x8*& vals, const uint32_t*& meta,
                   const uint8_t*& vidx, SsmmArgs& a) {
     const int64_t rc = compressed_rows(f, w_rows);
@@ -1527,34 +1666,17 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
   d.E_total = E_total;
   d.rows = H;
   d.K = F;
+  d.kper = pl.kper;
+  d.ksplit = pl.splits;
+  d.out_f32 = (float*)(ws + pl.extra_off);
 
-  // Tile shape by the mean bucket size: large buckets amortise weight traffic over 128 (160)
-  // tokens; small ones keep the token tile narrow so no MFMA work is spent on padding, give up the
-  // one-memory-instruction-per-MFMA placement (they are bound by HBM) and run two waves per SIMD.
-  // Template arguments: gate/up?, vector-wise?, stored row tiles per wave and matrix, token
-  // tiles per wave, waves along rows, waves along tokens, stages in flight + 1, waves per SIMD.
-  int shape = tile_shape(P, E_total);
-  if (const char* force = getenv("SSMM_TILE_SHAPE")) {   // tuning knob: 0..2 (never above what the workspace was sized for)
-    const int want = atoi(force);
-    if (want >= 0 && want <= 2 && (want == 2 || shape < 2)) shape = want;
-  }
-  int pipe = 2;
-  if (const char* force = getenv("SSMM_PIPE")) pipe = atoi(force);   // tuning knob: 1 = compiler-scheduled loop
-  int pipe_down = pipe;
-  // the hand-scheduled kernels address the token matrix with 32-bit offsets
-  if ((int64_t)T * H * 2 >= (int64_t)1 << 32) pipe = 1;
-  // plain 2:4: h is read in consecutive rows and the offsets count from a tile's first row
-  if (P * F * 2 >= (int64_t)1 << 32 && (is_vectorwise(f) || (int64_t)256 * F * 2 >= (int64_t)1 << 32)) pipe_down = 1;
-  if (gen) pipe = pipe_down = 1;
-  // Gathered formats, up to 64 pairs per expert: the down projection (reduction split, many blocks)
-  // is faster on 32-token tiles than on 64-token ones (measured); the first product only while one
-  // 32-token tile holds a bucket somewhat above the mean -- a second tile streams the weights again.
-  int gen_first_shape = shape;
-  if (gen && shape == 1 && P / E_total <= 64) {
-    const double mean = (double)(P / E_total);
-    shape = 0;
-    gen_first_shape = mean + 2.0 * sqrt(mean) <= 32.0 ? 0 : 1;
-  }
+  // Template arguments of the launches: gate/up?, vector-wise?, stored row tiles per wave and matrix,
+  // token tiles per wave, waves along rows, waves along tokens, stages in flight + 1, waves per SIMD
+  // (hand-scheduled kernels), split reduction?, activation kind from the call?.
+  // Large buckets amortise weight traffic over 128 (160) tokens; small ones keep the token tile
+  // narrow so no MFMA work is spent on padding, give up the one-memory-instruction-per-MFMA placement
+  // (they are bound by HBM) and run two waves per SIMD.
+  const int shape = pl.shape, gfs = pl.gen_first_shape, pipe = pl.pipe;
   const bool variant = activation != SSMM_ACT_SILU || !gated;   // kernels whose epilogue takes the activation kind from the call
   if (!mark(0)) return SSMM_EHIP;
   // First product.  Usual layer (SiLU, gated): hand-scheduled kernels; gathered formats and token
@@ -1569,38 +1691,16 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
       // the registers.  Small and medium ones: two blocks then fit a CU, which doubles the weight
       // bytes in flight (measured on the Mixtral shape, (4,8,32): first product 0.148 -> 0.118 ms
       // at 16 tokens, 0.31 -> 0.20 ms at 256).
-      st = gen_first_shape == 2   ? launch_ssmm<true, false, 1, 4, 4, 1, 3, true>(g, P, s)
-           : gen_first_shape == 1 ? launch_ssmm<true, false, 1, 2, 4, 1, 3, true>(g, P, s)
-                                  : launch_ssmm<true, false, 1, 1, 4, 1, 3, true>(g, P, s);
-    else if (pipe != 1) {
-      // The widest tile (256 output features x 128 tokens per block) also wins for small buckets, as
-      // long as it gives every CU a block: the weights stream once per expert whatever the tile, and
-      // the wide tile needs half the blocks and transfers per byte (measured on the Mixtral shape
-      // from 8 to 512 tokens: equal at 16 tokens, 8 % faster at 256, 21 % at 512).
-      int gshape = shape;
-      const int64_t active = P < E_total ? P : E_total;
-      const int64_t wide_blocks = (F + 255) / 256 * active * ((P / active + 127) / 128);
-      const int64_t wide_rows = (F + 255) / 256 * 256;   // rows the wide tiles stream (the last tile may hang over)
-      // (1,2,V): the narrow tiles stay ahead below 20 pairs per expert (measured); F = 1408: half a tile of overhang costs what the wide tile gains
-      if (!vec && wide_blocks >= 200 && (wide_rows - F) * 32 <= F) gshape = 2;
-      if (const char* force = getenv("SSMM_GU_SHAPE")) gshape = atoi(force);   // tuning knob: 0..2
-      // 128- or 160-token tiles for the wide shape: the 160-token tile reuses every weight operand
-      // five times instead of four (measured 3-11 % faster per token from 512 to 8192 tokens on the
-      // Mixtral shape) but pads more; it is taken when a bucket of mean + 2 sqrt(mean) pairs pads to
-      // at most 10 % more tokens with it.
-      const double est = (double)(P / active) + 2.0 * sqrt((double)(P / active));
-      const double pad4 = ceil(est / 128.0) * 128.0, pad5 = ceil(est / 160.0) * 160.0;
-      bool wide5 = pad5 <= 1.1 * pad4;
-      if (const char* force = getenv("SSMM_GU_NT5")) wide5 = atoi(force) == 1;   // tuning knob: 0 / 1
-      if (!vec && gshape == 2 && wide5)
-        st = launch_ssmm2<true, false, 2, 5, 4, 1, 3>(g, P, s);
-      else if (!vec)
-        st = gshape == 2   ? launch_ssmm2<true, false, 2, 4, 4, 1, 4>(g, P, s)
-             : gshape == 1 ? launch_ssmm2<true, false, 1, 4, 4, 1, 4>(g, P, s)
-                           : launch_ssmm2<true, false, 1, 1, 4, 1, 4, 2>(g, P, s);
-      else
-        st = gshape >= 1 ? launch_ssmm2<true, true, 1, 4, 4, 1, 4>(g, P, s) : launch_ssmm2<true, true, 1, 1, 4, 1, 4>(g, P, s);
-    }
+      st = gfs == 2   ? launch_ssmm<true, false, 1, 4, 4, 1, 3, true>(g, P, s)
+           : gfs == 1 ? launch_ssmm<true, false, 1, 2, 4, 1, 3, true>(g, P, s)
+                      : launch_ssmm<true, false, 1, 1, 4, 1, 3, true>(g, P, s);
+    else if (pipe != 1 && !vec)
+      st = pl.gshape == 2 && pl.wide5 ? launch_ssmm2<true, false, 2, 5, 4, 1, 3>(g, P, s)
+           : pl.gshape == 2           ? launch_ssmm2<true, false, 2, 4, 4, 1, 4>(g, P, s)
+           : pl.gshape == 1           ? launch_ssmm2<true, false, 1, 4, 4, 1, 4>(g, P, s)
+                                      : launch_ssmm2<true, false, 1, 1, 4, 1, 4, 2>(g, P, s);
+    else if (pipe != 1)
+      st = pl.gshape >= 1 ? launch_ssmm2<true, true, 1, 4, 4, 1, 4>(g, P, s) : launch_ssmm2<true, true, 1, 1, 4, 1, 4>(g, P, s);
     else if (!vec)   // fall-back kernels: 128-, 64- and 32-token tiles
       st = shape == 2   ? launch_ssmm<true, false, 2, 4, 4, 1, 3>(g, P, s)
            : shape == 1 ? launch_ssmm<true, false, 2, 2, 4, 1, 3>(g, P, s)
@@ -1611,8 +1711,8 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
                         : launch_ssmm<true, true, 1, 1, 4, 1, 3>(g, P, s);
   } else if (gated) {
     if (gen)
-      st = gen_first_shape >= 1 ? launch_ssmm<true, false, 1, 2, 4, 1, 3, true, true>(g, P, s)
-                                : launch_ssmm<true, false, 1, 1, 4, 1, 3, true, true>(g, P, s);
+      st = gfs >= 1 ? launch_ssmm<true, false, 1, 2, 4, 1, 3, true, true>(g, P, s)
+                    : launch_ssmm<true, false, 1, 1, 4, 1, 3, true, true>(g, P, s);
     else if (pipe != 1 && !vec && shape < 2)
       st = shape == 1 ? launch_ssmm2<true, false, 1, 4, 4, 1, 4, 1, false, true>(g, P, s)
                       : launch_ssmm2<true, false, 1, 1, 4, 1, 4, 2, false, true>(g, P, s);
@@ -1628,8 +1728,8 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
     // one weight matrix, activation in the epilogue: the single-matrix kernels (those of the
     // down projection, unsplit) with the token rows gathered through SEL
     if (gen)
-      st = gen_first_shape >= 1 ? launch_ssmm<false, false, 2, 2, 4, 1, 3, true, true>(g, P, s)
-                                : launch_ssmm<false, false, 1, 1, 4, 1, 3, true, true>(g, P, s);
+      st = gfs >= 1 ? launch_ssmm<false, false, 2, 2, 4, 1, 3, true, true>(g, P, s)
+                    : launch_ssmm<false, false, 1, 1, 4, 1, 3, true, true>(g, P, s);
     else if (pipe != 1 && !vec && shape < 2)
       st = shape == 1 ? launch_ssmm2<false, false, 2, 4, 4, 1, 4, 1, false, true>(g, P, s)
                       : launch_ssmm2<false, false, 2, 1, 4, 1, 4, 2, false, true>(g, P, s);
@@ -1645,90 +1745,33 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
   }
   if (st) return st;
   if (!mark(1)) return SSMM_EHIP;
-  int splits = 1;
-  if (pipe_down != 1) {
-    splits = down_splits(shape, P, H, F, E_total, f);
-    if (const char* force = getenv("SSMM_DOWN_SPLITS")) {   // tuning knob: 1..8
-      const int want = atoi(force);
-      if (want >= 1 && want <= 8 && shape < 2) splits = want;
+  // Down projection; with pl.splits > 1 the kernels write fp32 partial sums of the slices
+  const bool split = pl.splits > 1;
+  if (pl.pipe_down != 1 && !vec) {
+    switch (pl.down_kernel) {
+      case kDownMedium5:
+        st = split ? launch_ssmm2<false, false, 2, 5, 4, 1, 3, 1, true>(d, P, s) : launch_ssmm2<false, false, 2, 5, 4, 1, 3>(d, P, s);
+        break;
+      case kDownHalf:
+        st = launch_ssmm2<false, false, 2, 5, 4, 1, 3>(d, P, s);
+        break;
+      case kDownTall:
+        st = split ? launch_ssmm2<false, false, 4, 5, 4, 1, 3, 1, true>(d, P, s) : launch_ssmm2<false, false, 4, 5, 4, 1, 3>(d, P, s);
+        break;
+      case kDownMedium:
+        st = split ? launch_ssmm2<false, false, 2, 4, 4, 1, 4, 1, true>(d, P, s) : launch_ssmm2<false, false, 2, 4, 4, 1, 4>(d, P, s);
+        break;
+      default:
+        st = split ? launch_ssmm2<false, false, 2, 1, 4, 1, 4, 2, true>(d, P, s) : launch_ssmm2<false, false, 2, 1, 4, 1, 4, 2>(d, P, s);
     }
-    const int KS = F / kStageK;
-    d.kper = (KS + splits - 1) / splits;
-    d.ksplit = splits = (KS + d.kper - 1) / d.kper;   // no empty split
-    d.out_f32 = (float*)((char*)workspace + align256((size_t)P * F * 2) + align256((size_t)P * H * 2));
-    // 160-token tiles for the large buckets of the down projection (its few, long blocks then
-    // fill the last round of the chip better)
-    int dshape = shape;
-    if (const char* force = getenv("SSMM_DOWN_SHAPE")) {   // tuning knob: 1 = the medium tile (unsplit) where the large one was chosen
-      if (atoi(force) == 1 && shape == 2) dshape = 1;
-    }
-    // large buckets, but so few of them that 512-row tiles would leave CUs without a block: half-height tiles
-    const int64_t active_d = P < E_total ? P : E_total;
-    const double est_d = (double)(P / active_d) + 2.0 * sqrt((double)(P / active_d));   // a bucket somewhat above the mean
-    const int64_t tall_blocks = tall_down_blocks(P, H, E_total, f);
-    bool half_height = dshape == 2 && tall_blocks <= 160;   // measured on the Mixtral shape: 5-6 % at 768 and 1024 tokens
-    if (const char* force = getenv("SSMM_DOWN_HALF")) half_height = dshape == 2 && atoi(force) == 1;   // tuning knob: 0 / 1
-    int tall_splits = dshape == 2 && !expanded ? tall_down_splits(P, H, F, E_total, f) : 1;
-    if (const char* force = getenv("SSMM_DOWN_TALLSPLIT")) {   // tuning knob: 0 = no split of the large tile's reduction
-      if (atoi(force) == 0) tall_splits = 1;
-    }
-    const bool tall_split = tall_splits > 1;
-    if (tall_split) {
-      half_height = false;
-      d.kper = (KS + tall_splits - 1) / tall_splits;
-      d.ksplit = splits = (KS + d.kper - 1) / d.kper;   // no empty slice
-    }
-    // medium buckets that one 160-token tile holds but a 128-token tile does not (a second,
-    // nearly empty tile would stream the expert's weights again)
-    bool medium5 = dshape == 1 && ceil(est_d / 160.0) < ceil(est_d / 128.0);
-    if (const char* force = getenv("SSMM_DOWN_NT5")) medium5 = dshape == 1 && atoi(force) == 1;   // tuning knob: 0 / 1
-    if (!vec && medium5) {
-      splits = down_splits(shape, P, H, F, E_total, f, 160);
-      if (const char* force = getenv("SSMM_DOWN_SPLITS")) {
-        const int want = atoi(force);
-        if (want >= 1 && want <= 8 && shape < 2) splits = want;   // the workspace holds 8 slices only for these shapes
-      }
-      d.kper = (KS + splits - 1) / splits;
-      d.ksplit = splits = (KS + d.kper - 1) / d.kper;
-    }
-    if (!vec && medium5)
-      st = splits > 1 ? launch_ssmm2<false, false, 2, 5, 4, 1, 3, 1, true>(d, P, s) : launch_ssmm2<false, false, 2, 5, 4, 1, 3>(d, P, s);
-    else if (!vec && half_height)
-      st = launch_ssmm2<false, false, 2, 5, 4, 1, 3>(d, P, s);
-    else if (!vec && tall_split)
-      st = launch_ssmm2<false, false, 4, 5, 4, 1, 3, 1, true>(d, P, s);
-    else if (!vec)
-      st = dshape == 2   ? launch_ssmm2<false, false, 4, 5, 4, 1, 3>(d, P, s)
-           : dshape == 1 ? (splits > 1 ? launch_ssmm2<false, false, 2, 4, 4, 1, 4, 1, true>(d, P, s)
-                                      : launch_ssmm2<false, false, 2, 4, 4, 1, 4>(d, P, s))
-                        : (splits > 1 ? launch_ssmm2<false, false, 2, 1, 4, 1, 4, 2, true>(d, P, s)
-                                      : launch_ssmm2<false, false, 2, 1, 4, 1, 4, 2>(d, P, s));
-    else
-      st = shape == 2   ? launch_ssmm2<false, true, 2, 4, 4, 1, 4>(d, P, s)
-           : shape == 1 ? (splits > 1 ? launch_ssmm2<false, true, 1, 4, 4, 1, 4, 1, true>(d, P, s)
-                                      : launch_ssmm2<false, true, 1, 4, 4, 1, 4>(d, P, s))
-                        : (splits > 1 ? launch_ssmm2<false, true, 1, 1, 4, 1, 4, 2, true>(d, P, s)
-                                      : launch_ssmm2<false, true, 1, 1, 4, 1, 4, 2>(d, P, s));
+  } else if (pl.pipe_down != 1) {
+    st = shape == 2   ? launch_ssmm2<false, true, 2, 4, 4, 1, 4>(d, P, s)
+         : shape == 1 ? (split ? launch_ssmm2<false, true, 1, 4, 4, 1, 4, 1, true>(d, P, s)
+                               : launch_ssmm2<false, true, 1, 4, 4, 1, 4>(d, P, s))
+                      : (split ? launch_ssmm2<false, true, 1, 1, 4, 1, 4, 2, true>(d, P, s)
+                               : launch_ssmm2<false, true, 1, 1, 4, 1, 4, 2>(d, P, s));
   } else if (gen) {
-    // small buckets: few rows per block and the reduction split, so that every CU has blocks to
-    // stream weights with (the partial sums go the way of the hand-scheduled kernels' split)
-    if (shape < 2 && P * F * 2 < (int64_t)1 << 32) {
-      const int rows_per_block = shape == 1 ? 256 : 128, NBg = shape == 1 ? 64 : 32;
-      const int64_t active = P < E_total ? P : E_total;
-      const int64_t blocks = (H + rows_per_block - 1) / rows_per_block * active * ((P / active + NBg - 1) / NBg);
-      splits = (int)((1024 + blocks / 2) / blocks);   // measured on the Mixtral shape at 16 and 256 tokens: four and two splits
-      splits = splits < 1 ? 1 : splits > 8 ? 8 : splits;
-      if (const char* force = getenv("SSMM_DOWN_SPLITS")) {   // tuning knob: 1..8
-        const int want = atoi(force);
-        if (want >= 1 && want <= 8) splits = want;
-      }
-      const int KS = F / kStageK;
-      while (splits > 1 && KS / splits < 8) splits--;
-      d.kper = (KS + splits - 1) / splits;
-      d.ksplit = splits = (KS + d.kper - 1) / d.kper;   // no empty split
-      d.out_f32 = (float*)((char*)workspace + align256((size_t)P * F * 2) + align256((size_t)P * H * 2));
-    }
-    if (splits > 1)
+    if (split)
       st = shape == 1 ? launch_ssmm<false, false, 2, 2, 4, 1, 3, true, false, true>(d, P, s)
                       : launch_ssmm<false, false, 1, 1, 4, 1, 3, true, false, true>(d, P, s);
     else
@@ -1747,9 +1790,9 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
   if (st) return st;
   if (!mark(2)) return SSMM_EHIP;
   const int64_t total = (int64_t)T * (H / 8);
-  if (splits > 1)
+  if (split)
     hipLaunchKernelGGL(combine_split_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                       (const float*)d.out_f32, inv, sel_w, T, H, slots, splits, P, y);
+                       (const float*)d.out_f32, inv, sel_w, T, H, slots, pl.splits, P, y);
   else
     hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const uint16_t*)yp, inv,
                        T, H, slots, y);
@@ -1799,7 +1842,7 @@ inline int matmul_splits(int64_t rows, int64_t K, int n, ssmm_format f) {
   const int rows_per_block = (shape == 2 ? 512 : 256) / (vec ? 2 : 1);            // stored rows
   const int NB = shape == 2 ? 160 : shape == 1 ? 128 : 32;
   const int64_t blocks = (rc + rows_per_block - 1) / rows_per_block * ((n + NB - 1) / NB);
-  int most = (int)(256 / blocks);
+  int most = (int)(compute_units() / blocks);
   most = most < 1 ? 1 : most > 8 ? 8 : most;
   const int KS = (int)(K / kStageK);
   // a slice costs its chain of stages; the partial sums are written and read once at about 4 TB/s,
@@ -1860,9 +1903,7 @@ extern "C" int ssmm_matmul(const void* a_tiled, int64_t rows, int64_t K, ssmm_fo
   // same tile shapes as the down projection of the expert FFN (one "expert" with n tokens)
   const int shape = tile_shape(n, 1);
   int splits = matmul_splits(rows, K, n, f);
-  if (const char* force = getenv("SSMM_MATMUL_SPLITS")) {   // tuning knob: 1 = no split
-    if (atoi(force) == 1) splits = 1;
-  }
+  if (knob("SSMM_MATMUL_SPLITS") == 1) splits = 1;   // tuning knob: no split
   if (splits > 1) {
     const int KS = (int)(K / kStageK);
     d.kper = (KS + splits - 1) / splits;

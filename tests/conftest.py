@@ -25,3 +25,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def tuning_library():
+    """The test's calls go to libssmm_tune.so, whose dispatch rules read override knobs from the
+    environment (the library proper has none): for tests that force a code path."""
+    from paper_2503_10725_amd import binding as B
+    with B.tuning_library() as handle:
+        yield handle

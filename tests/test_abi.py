@@ -167,29 +167,87 @@ def test_build_rejects_hand_scheduled_kernels_that_park_registers_in_accumulatio
     assert build.agpr_parkers(report) == [bad]
 
 
-def test_assembly_audit_finds_registers_saved_while_their_load_is_in_flight():
-    """The optional audit (python -m paper_2503_10725_amd.build --audit) scans device assembly of the
-    hand-scheduled kernels; here on a hand-written snippet."""
+def test_assembly_check_finds_every_access_to_a_register_whose_load_is_in_flight():
+    """The build scans the device assembly of the hand-scheduled kernels (build.in_flight_hazards); here on
+    hand-written snippets: a copy, a save to an accumulation register, a spill, an MFMA behind a wait that
+    counts one load too few, and a use that is only wrong along the loop's back edge."""
     from paper_2503_10725_amd import build
-    asm = """
-_ZN4ssmm12ssmm_kernel2ILb1ELb0ELi1ELi1ELi4ELi1ELi4ELi2ELb0ELb0EEEvNS_8SsmmArgsE:
+    k2 = "_ZN4ssmm12ssmm_kernel2ILb1ELb0ELi1ELi1ELi4ELi1ELi4ELi2ELb0ELb0EEEvNS_8SsmmArgsE"
+    asm = (k2 + """:
 	;;#ASMSTART
 	global_load_dwordx4 v[40:43], v0, s[34:35] offset:0x400
 	;;#ASMEND
 	v_accvgpr_write_b32 a40, v41
 	v_accvgpr_write_b32 a41, v7
-	scratch_store_dword off, v9, s32
+	v_mov_b32_e32 v50, v43
+	scratch_store_dword off, v40, s32
+	v_add_u32_e32 v9, v8, v7
 	s_waitcnt vmcnt(0)
 	v_accvgpr_write_b32 a42, v42
-	scratch_load_dword v9, off, s32
+	v_mov_b32_e32 v51, v43
 	s_endpgm
+.Lfunc_end0:
 _ZN4ssmm11ssmm_kernelILb0EEEvNS_8SsmmArgsE:
 	;;#ASMSTART
 	global_load_dwordx4 v[40:43], v0, s[34:35]
 	;;#ASMEND
 	v_accvgpr_write_b32 a40, v41
 	s_endpgm
-""".split("\n")
+""").split("\n")
     found = build.in_flight_hazards(asm)
-    assert [t for _, _, t in found] == ["v_accvgpr_write_b32 a40, v41", "scratch_store_dword off, v9, s32"]
-    assert all(k.startswith("_ZN4ssmm12ssmm_kernel2") for k, _, _ in found)
+    assert [(t, r) for _, _, t, r in found] == [("v_accvgpr_write_b32 a40, v41", 41), ("v_mov_b32_e32 v50, v43", 43),
+                                               ("scratch_store_dword off, v40, s32", 40)]
+    assert all(k == k2 for k, _, _, _ in found)
+
+    # loads return in order: vmcnt(N) covers a load once N or fewer were issued behind it
+    counts = (k2 + """:
+	;;#ASMSTART
+	global_load_dwordx4 v[10:13], v0, s[34:35]
+	;;#ASMEND
+	;;#ASMSTART
+	global_load_dwordx4 v[14:17], v0, s[34:35]
+	;;#ASMEND
+	;;#ASMSTART
+	global_load_lds_dwordx4 v1, s[36:37]
+	;;#ASMEND
+	;;#ASMSTART
+	s_waitcnt vmcnt(2)
+	;;#ASMEND
+	;;#ASMSTART
+	v_smfmac_f32_32x32x32_bf16 a[0:15], v[10:13], v[20:27], v30
+	;;#ASMEND
+	;;#ASMSTART
+	v_smfmac_f32_32x32x32_bf16 a[0:15], v[14:17], v[20:27], v30
+	;;#ASMEND
+	;;#ASMSTART
+	s_waitcnt vmcnt(1)
+	;;#ASMEND
+	;;#ASMSTART
+	v_smfmac_f32_32x32x32_bf16 a[0:15], v[14:17], v[20:27], v30
+	;;#ASMEND
+	s_endpgm
+""").split("\n")
+    found = build.in_flight_hazards(counts)
+    assert sorted({r for _, _, _, r in found}) == [14, 15, 16, 17] and len({n for _, n, _, _ in found}) == 1
+
+    # a load at the end of a loop body is still in flight at the top of the next pass
+    loop = (k2 + """:
+	s_mov_b32 s0, 0
+.LBB0_1:
+	v_add_u32_e32 v5, v12, v6
+	;;#ASMSTART
+	s_waitcnt vmcnt(0)
+	;;#ASMEND
+	v_add_u32_e32 v5, v13, v6
+	;;#ASMSTART
+	global_load_dwordx4 v[10:13], v0, s[34:35]
+	;;#ASMEND
+	s_add_i32 s0, s0, 1
+	s_cmp_lt_i32 s0, 8
+	s_cbranch_scc1 .LBB0_1
+	s_waitcnt vmcnt(0)
+	v_add_u32_e32 v5, v13, v6
+	s_endpgm
+""").split("\n")
+    found = build.in_flight_hazards(loop)
+    assert [(t, r) for _, _, t, r in found] == [("v_add_u32_e32 v5, v12, v6", 12)]

@@ -162,7 +162,7 @@ def test_unpruned_weights_through_the_pair_embedding_equal_a_dense_ffn():
 
 @pytest.mark.parametrize("fmt", [(1, 1, 0), (1, 2, 8)], ids=["2:4", "1:2:8"])
 @pytest.mark.parametrize("T", [24, 200, 240], ids=["32-token-tiles", "128-token-tiles", "160-token-tiles"])
-def test_split_down_projection(monkeypatch, fmt, T):
+def test_split_down_projection(monkeypatch, tuning_library, fmt, T):
     """Small buckets split the reduction of the down projection into fp32 partial sums.  Every
     number of splits (also one that leaves a ragged last slice: 24 stages in 5 slices) must meet
     the oracle, and the result may differ between split counts only by fp32 summation order."""
@@ -184,7 +184,7 @@ def test_split_down_projection(monkeypatch, fmt, T):
 
 
 @pytest.mark.parametrize("H,F", [(512, 1536), (320, 1600)], ids=["3x8-stages", "ragged-slices-odd-rows"])
-def test_split_down_projection_of_few_large_buckets(monkeypatch, H, F):
+def test_split_down_projection_of_few_large_buckets(monkeypatch, tuning_library, H, F):
     """Large buckets, but few blocks: the 512-row x 160-token down tile splits its reduction into
     up to four slices of at least eight stages (24 stages: 3 slices of 8; 25 stages: 9 + 9 + 7).  Split
     and unsplit must both meet the oracle and differ only by summation order and one bf16 rounding."""
@@ -273,7 +273,7 @@ def test_variant_argument_checks():
 
 # ---- the compiler-scheduled kernels as the fall-back of the usual layer (token matrices of 4 GB and more take them) ----
 @pytest.mark.parametrize("name", ["tiny", "mid_shared", "big", "odd_rows_big", "vec_mid", "vec_big_shared", "loop_big"])
-def test_fallback_kernels_match_oracle(monkeypatch, name):
+def test_fallback_kernels_match_oracle(monkeypatch, tuning_library, name):
     monkeypatch.setenv("SSMM_PIPE", "1")
     run_case(next(c for c in SMALL if c.name == name))
 
