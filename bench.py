@@ -258,6 +258,51 @@ def mfma_probe(torch, out_path=None):
     return rows
 
 
+def subrow_ab(torch, B, synth, steps, warmup, out_path=None, tokens=4096):
+    """Sub-Row compute skipping against the masked scheme (sections 4.1 / 4.3 on this hardware), Mixtral
+    shape, formats (1,2,V)+2:4 for V = 32 ... 1024: the layer on (a) the default kernels (hand-scheduled,
+    every stored operand multiplied once per source row, masked), (b) the same masked scheme on the
+    compiler-scheduled kernels with 64-token tiles and (c) the compute-skipping kernels (same family, same
+    tiles: one MFMA per stored operand into intermediate sums, merged by source-row bit every V/32 k
+    blocks).  (b) and (c) differ in the scheme only.  The knobs that choose (b) and (c) exist in the
+    tuning build of the library (libssmm_tune.so), which this leg loads."""
+    import dataclasses
+    rows = []
+    base = synth.CONFIGS["mixtral75"]
+    variants = [("masked, hand-scheduled (default)", {}),
+                ("masked, compiler-scheduled, 64-token tiles", {"SSMM_PIPE": "1", "SSMM_TILE_SHAPE": "1"}),
+                ("compute skipping, compiler-scheduled, 64-token tiles", {"SSMM_SUBROW_SKIP": "1", "SSMM_TILE_SHAPE": "1"})]
+    with B.tuning_library():
+        for V in (32, 64, 128, 256, 512, 1024):
+            cfg = dataclasses.replace(base, fmt=(1, 2, V)).with_tokens(tokens)
+            dense = synth.make_weights(cfg, "cuda")
+            enc = [B.compress_weights(w, cfg.fmt, canonical=True, tiled=True)["tiled"] for w in dense]
+            del dense
+            torch.cuda.synchronize()
+            for name, env in variants:
+                for k, v in env.items():
+                    os.environ[k] = v
+                try:
+                    pt = run_point(cfg, enc, steps, warmup, B, synth, torch)
+                finally:
+                    for k in env:
+                        del os.environ[k]
+                rows.append({"V": V, "variant": name, "ms_per_step": pt["ms_per_step"], "gate_up_ms": pt["kernel_ms"]["gate_up"],
+                             "down_ms": pt["kernel_ms"]["down"], "tflops_dense_equiv": pt["tflops_dense_equiv"]})
+            del enc
+            torch.cuda.empty_cache()
+    if out_path:
+        with open(out_path, "w") as f:
+            f.write("# Sub-Row compute skipping against the masked scheme: Mixtral-shaped layer (H 4096, F 14336, 8 experts top-2), %d tokens, (1,2,V)+2:4 weights, one MI355X\n" % tokens)
+            f.write("# command: python3 bench.py --subrow-ab <this file>\n")
+            f.write("# whole step (route .. combine) and its two SSMM kernels from HIP events; mean of %d steps\n" % steps)
+            f.write("# V | variant | ms per step | gate/up ms | down ms | dense-equiv TFLOP/s\n")
+            for r in rows:
+                f.write("%4d | %-52s | %7.4f | %7.4f | %7.4f | %7.1f\n" % (r["V"], r["variant"], r["ms_per_step"], r["gate_up_ms"],
+                                                                          r["down_ms"], r["tflops_dense_equiv"]))
+    return rows
+
+
 def ssmm_grid(torch, B, out_path=None):
     """Stand-alone kernel benchmark (the paper's section 6.1): C = A x B[:, SEL] over a grid of
     (m, k, n) in 256..16384 (the paper's own 238 sizes are not listed; powers of four and the
@@ -366,6 +411,9 @@ def main():
     ap.add_argument("--mfma-probe", metavar="FILE", default=None,
                     help="instead of the layer benchmark: time back-to-back matrix instructions (the kernels' sparse MFMA by "
                          "operand bits, the other sparse shape, the dense MFMA), write the table to FILE")
+    ap.add_argument("--subrow-ab", metavar="FILE", default=None,
+                    help="instead of the layer benchmark: Sub-Row compute skipping against the masked scheme for (1,2,V), "
+                         "V = 32..1024, on the Mixtral shape; write the table to FILE")
     ap.add_argument("--ssmm-grid", metavar="FILE", default=None,
                     help="instead of the layer benchmark: time the stand-alone SSMM over a shape grid, write the table to FILE")
     args = ap.parse_args()
@@ -384,6 +432,10 @@ def main():
     if args.mfma_probe:
         rows = mfma_probe(torch, args.mfma_probe)
         print(json.dumps({"metric": "sustained matrix-instruction rate by instruction and operand bits", "rows": rows}))
+        return
+    if args.subrow_ab:
+        rows = subrow_ab(torch, B, synth, args.steps, args.warmup, args.subrow_ab)
+        print(json.dumps({"metric": "Sub-Row compute skipping vs the masked scheme, ms per layer step", "rows": rows}))
         return
     if args.ssmm_grid:
         rows = ssmm_grid(torch, B, args.ssmm_grid)

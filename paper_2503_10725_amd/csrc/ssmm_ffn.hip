@@ -69,6 +69,7 @@ struct SsmmArgs {
   int K;                          // reduction length
   int actfn;                      // SSMM_ACT_*; 0: none.  gate/up kernels: h = act(gate) * up; others: out = act(sum), or sum * routing weight when 0
   int gN, gM;                     // gathered formats: N and M; row_tiles then counts DENSE 32-row tiles
+  int vper;                       // compute-skipping kernels: k blocks of 32 per Sub-Row (V / 32)
   int stored_tiles;               // gathered formats: 32-row tiles of the stored matrix of one expert
   int n_tiles_max;                // upper bound on token tiles over all experts
   // split reduction (down projection of small buckets): block (.., split) multiplies stages
@@ -205,9 +206,20 @@ __device__ inline uint32_t lds_address(const void* p) {
 // the index words of the two k blocks of a stage may come from different stored rows and are
 // kept apart (the MFMA of k block 0 reads the low half of one, that of k block 1 the high half of
 // the other).  MFMA work equals the plain 2:4 case, weight bytes shrink by N/M.
-template <bool GATEUP, bool VEC, int MT, int NT, int WM, int WN, int DS, bool GEN = false>
+//
+// SKIP (with VEC, V a multiple of 32): the compute skipping of sections 4.1 and 4.3 as far as this
+// hardware allows it.  A Sub-Row then covers whole k blocks of the MFMA, so every stored operand is
+// issued ONCE, into an intermediate accumulator tile (the paper's C_IR), and at the end of every
+// V-wide block of the reduction the intermediate sums are moved to the accumulators of the dense rows
+// they belong to: register r of a lane holds the same stored row in the intermediate tile and in the
+// tiles of its two candidate dense rows, so the move is a selected add per register, by the source-row
+// bit of the stored row in that block, and no value changes lanes.  Half the MFMAs of the masked
+// scheme, plus two vector instructions and more per accumulator register and block -- measured
+// against the masked scheme (bench.py --subrow-ab); it is not what the layer runs by default.
+template <bool GATEUP, bool VEC, int MT, int NT, int WM, int WN, int DS, bool GEN = false, bool SKIP = false>
 struct SsmmTile {
   static_assert(!(VEC && GEN), "one of the two vector-wise schemes");
+  static_assert(!SKIP || VEC, "compute skipping is a way to run the (1,2,V) format");
   static constexpr int DB = 2 * DS;                // token-tile buffers
   static constexpr int NTH = 64 * WM * WN;
   static constexpr int NB = 32 * NT * WN;          // tokens per block tile
@@ -235,6 +247,8 @@ struct SsmmTile {
   uint32_t lane_i2, half32;  // GEN: 2 * MFMA row of the lane, 32 * its half
   uint32_t vx[DS][NA];       // VEC: 2 bits per k block (bits 0-1: first, bits 8-9: second k block)
   f32x16 acc[NA * NP][NT];   // VEC: accumulator 2x = even dense rows, 2x+1 = odd dense rows of stream x
+  f32x16 tmp[SKIP ? NA : 1][NT];   // SKIP: intermediate sums of the stored rows over the current V-wide block
+  int vper, ph_shift;              // SKIP: k blocks per Sub-Row (V / 32); 4 * (lane / 32)
 
   // ---- loads of one stage, as NA + CH separate tasks so that they can be spread between MFMAs
   // (a wave issues in order: a block of address arithmetic and loads in one place would leave
@@ -323,6 +337,63 @@ struct SsmmTile {
   }
   // Token tile outermost: the first MFMAs need only the first token operand, and an operand
   // register is free for the next k block as soon as its MFMAs have been issued.
+  // SKIP: intermediate sums -> accumulators of the dense rows, by the source-row bits of k block kb of the stage
+  template <int SET>
+  __device__ inline void merge(int kb) {
+#pragma unroll
+    for (int x = 0; x < NA; x++) {
+      // bit i: MFMA row i of the stored tile came from the odd row of its pair (both lane halves hold it)
+      const uint32_t rowbits = (uint32_t)__ballot(((vx[SET][x] >> (8 * kb)) & 1u) != 0);
+      // register r of lane (token, half h) is stored row 16 h + r of the tile = MFMA row 8 (r / 4) + 4 h + r % 4
+      const uint32_t mine = rowbits >> ph_shift;
+#pragma unroll
+      for (int n = 0; n < NT; n++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const bool odd = (mine >> (8 * (r / 4) + r % 4)) & 1u;
+          const float v = tmp[x][n][r];
+          acc[2 * x + 1][n][r] += odd ? v : 0.f;
+          acc[2 * x][n][r] += odd ? 0.f : v;
+          tmp[x][n][r] = 0.f;
+        }
+    }
+  }
+  // SKIP: one MFMA per stored operand and token tile (the compiler's own MFMA: it places the wait
+  // states between the matrix pipe and the vector instructions of the merge)
+  template <int SET, int BUF>
+  __device__ inline void multiply_skip(const uint4* lds, bool more, bool tokens, int s) {
+    constexpr int LSET = (SET + DS - 1) % DS, LBUF = (BUF + DB - 1) % DB;
+    const uint4* base = lds + BUF * (NB * 8);
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) {
+      bf16x16 bf[NT];
+#pragma unroll
+      for (int n = 0; n < NT; n++) bf[n] = read_b(base, n, kb);
+#pragma unroll
+      for (int n = 0; n < NT; n++)
+#pragma unroll
+        for (int x = 0; x < NA; x++) {
+          if (kb == 0) tmp[x][n] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[SET][x][0], bf[n], tmp[x][n], (int)idx[SET][x], 0, 0);
+          else tmp[x][n] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a[SET][x][1], bf[n], tmp[x][n], (int)idx[SET][x], 0, 1);
+        }
+      if ((2 * s + kb + 1) % vper == 0) merge<SET>(kb);   // uniform over the wave
+      if (kb == 0) {   // this step's loads, in two halves
+#pragma unroll
+        for (int t = 0; t < NA + CH; t++)
+          if (t % 2 == 0) {
+            if (t < NA) issue_a_stream<LSET>(t, more);
+            else if (tokens) issue_b_chunk<LBUF>(t - NA);
+          }
+      } else {
+#pragma unroll
+        for (int t = 0; t < NA + CH; t++)
+          if (t % 2 == 1) {
+            if (t < NA) issue_a_stream<LSET>(t, more);
+            else if (tokens) issue_b_chunk<LBUF>(t - NA);
+          }
+      }
+    }
+  }
   template <int SET, int BUF>
   __device__ inline void multiply(const uint4* lds, bool more, bool tokens) {
     constexpr int LSET = (SET + DS - 1) % DS, LBUF = (BUF + DB - 1) % DB;   // where this step's loads go
@@ -392,7 +463,8 @@ struct SsmmTile {
       if (GEN) require_landed(idx1[SET][x]);
     }
     block_barrier();
-    multiply<SET, BUF>(lds, s + DS < KS, s + DB - 1 < KS);
+    if constexpr (SKIP) multiply_skip<SET, BUF>(lds, s + DS < KS, s + DB - 1 < KS, s);
+    else multiply<SET, BUF>(lds, s + DS < KS, s + DB - 1 < KS);
   }
   // the last KS % (2 DS) steps: nested, so that no later step follows a skipped one
   template <int U>
@@ -411,10 +483,10 @@ struct SsmmTile {
 
 // SPLITK: the block multiplies one slice of the reduction and writes unscaled fp32 partial sums
 // (single-matrix kernels without activation only)
-template <bool GATEUP, bool VEC, int MT, int NT, int WM, int WN, int DS, bool GEN = false, bool ANYACT = false, bool SPLITK = false>
+template <bool GATEUP, bool VEC, int MT, int NT, int WM, int WN, int DS, bool GEN = false, bool ANYACT = false, bool SPLITK = false, bool SKIP = false>
 __global__ void __launch_bounds__(64 * WM * WN) ssmm_kernel(const SsmmArgs p) {
   static_assert(!(SPLITK && (GATEUP || ANYACT || VEC)), "partial sums: one matrix, no activation, plain or gathered format");
-  using Tile = SsmmTile<GATEUP, VEC, MT, NT, WM, WN, DS, GEN>;
+  using Tile = SsmmTile<GATEUP, VEC, MT, NT, WM, WN, DS, GEN, SKIP>;
   constexpr int NTH = Tile::NTH, NB = Tile::NB, NA = Tile::NA, CH = Tile::CH, NP = Tile::NP;
   __shared__ uint4 lds[Tile::DB * NB * 8];   // token-tile ring
 
@@ -514,6 +586,16 @@ __global__ void __launch_bounds__(64 * WM * WN) ssmm_kernel(const SsmmArgs p) {
     for (int n = 0; n < NT; n++)
 #pragma unroll
       for (int r = 0; r < 16; r++) t.acc[x][n][r] = 0.f;
+  if (SKIP) {
+    t.vper = p.vper;
+    t.ph_shift = 4 * t.ph;
+#pragma unroll
+    for (int x = 0; x < NA; x++)
+#pragma unroll
+      for (int n = 0; n < NT; n++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) t.tmp[x][n][r] = 0.f;
+  }
 
   // ---- prologue: token tiles of the first 2 DS - 1 stages, then A operands of the first DS - 1
   constexpr int DB = Tile::DB;
@@ -533,10 +615,11 @@ __global__ void __launch_bounds__(64 * WM * WN) ssmm_kernel(const SsmmArgs p) {
   t.template tail<0>(s, KS, lds);
   drain_mfma();
   // whatever reads the sums reads them behind the drain (asm statements keep their order)
+  if (!SKIP)
 #pragma unroll
-  for (int x = 0; x < NA * NP; x++)
+    for (int x = 0; x < NA * NP; x++)
 #pragma unroll
-    for (int n = 0; n < NT; n++) asm volatile("" : "+a"(t.acc[x][n]));
+      for (int n = 0; n < NT; n++) asm volatile("" : "+a"(t.acc[x][n]));
 
   // ---- epilogue: lane (j, ph) holds, per (stored row tile, token tile), 16 consecutive stored
   // rows 16*ph .. 16*ph+15 of token j.  Plain 2:4: these are 16 consecutive output features (two
@@ -1321,7 +1404,7 @@ inline int tall_down_splits(int64_t P, int H, int F, int E_total, ssmm_format f)
   return S;
 }
 
-template <bool GATEUP, bool VEC, int MT, int NT, int WM, int WN, int DS, bool GEN = false, bool ANYACT = false, bool SPLITK = false>
+template <bool GATEUP, bool VEC, int MT, int NT, int WM, int WN, int DS, bool GEN = false, bool ANYACT = false, bool SPLITK = false, bool SKIP = false>
 int launch_ssmm(SsmmArgs a, int64_t P, hipStream_t s) {
   constexpr int NB = 32 * NT * WN;
   DeviceShape dev;
@@ -1332,7 +1415,7 @@ int launch_ssmm(SsmmArgs a, int64_t P, hipStream_t s) {
   a.n_tiles_max = (int)((P + NB - 1) / NB) + a.E_total;   // every expert adds at most one ragged tile
   int64_t grid = (int64_t)MTB * a.n_tiles_max;
   grid = (grid + kXcdGroups - 1) / kXcdGroups * kXcdGroups;
-  auto kern = ssmm_kernel<GATEUP, VEC, MT, NT, WM, WN, DS, GEN, ANYACT, SPLITK>;
+  auto kern = ssmm_kernel<GATEUP, VEC, MT, NT, WM, WN, DS, GEN, ANYACT, SPLITK, SKIP>;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * WM * WN), 0, s, a);
   SSMM_RETURN_IF_LAUNCH_FAILED();
   return SSMM_OK;
@@ -1423,11 +1506,15 @@ inline bool expands_weights(ssmm_format f, int64_t P, int E_total) {
 // What one call of the layer launches, decided on the host from its shapes alone (the bucket sizes
 // stay on the device, so the rules work with a bucket "somewhat above the mean").  The workspace
 // size and the call itself both read this plan, so they cannot disagree.
+#ifndef SKIP_NT
+#define SKIP_NT 2   // token tiles of 32 per wave on the compute-skipping kernels (their accumulators live in vector registers)
+#endif
 enum DownKernel { kDownSmall, kDownMedium, kDownMedium5, kDownHalf, kDownTall };
 struct FfnPlan {
   int64_t P;
   bool expanded;         // gathered format multiplied as plain 2:4 operands expanded into the workspace
   bool gen, vec;         // format class the kernels see: gathered / (1,2,V) masked / neither (plain 2:4)
+  bool skip;             // (1,2,V), V % 32 == 0, on the compute-skipping kernels (tuning knob; the masked ones are the default)
   int shape;             // tile class by mean bucket size (tile_shape), lowered for small gathered buckets
   int gen_first_shape;   // gathered formats: tile class of the first product
   int pipe, pipe_down;   // 2: hand-scheduled kernels, 1: compiler-scheduled ones
@@ -1455,6 +1542,8 @@ inline FfnPlan plan_ffn(int T, int H, int F, int E_total, int slots, ssmm_format
   // plain 2:4: h is read in consecutive rows and the offsets count from a tile's first row
   if (P * F * 2 >= (int64_t)1 << 32 && (is_vectorwise(fk) || (int64_t)256 * F * 2 >= (int64_t)1 << 32)) pl.pipe_down = 1;
   if (pl.gen) pl.pipe = pl.pipe_down = 1;
+  pl.skip = pl.vec && fk.V % 32 == 0 && knob("SSMM_SUBROW_SKIP") == 1;
+  if (pl.skip) pl.pipe = pl.pipe_down = 1;   // built on the compiler-scheduled kernels
   // Gathered formats, up to 64 pairs per expert: the down projection (reduction split, many blocks)
   // is faster on 32-token tiles than on 64-token ones (measured); the first product only while one
   // 32-token tile holds a bucket somewhat above the mean -- a second tile streams the weights again.
@@ -1655,6 +1744,7 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
   g.rows = F;
   g.K = H;
   g.actfn = activation;
+  g.vper = f.V / 32;
 
   SsmmArgs d = {};
   d.act = h;
@@ -1666,6 +1756,7 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
   d.E_total = E_total;
   d.rows = H;
   d.K = F;
+  d.vper = f.V / 32;
   d.kper = pl.kper;
   d.ksplit = pl.splits;
   d.out_f32 = (float*)(ws + pl.extra_off);
@@ -1685,7 +1776,10 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
   // small and medium tile shapes, compiler-scheduled where the generic epilogue does not fit
   // the register budget of the hand-scheduled form (every kernel here must compile without
   // spills: the build checks it).
-  if (!variant) {
+  if (!variant && pl.skip) {
+    st = shape >= 1 ? launch_ssmm<true, true, 1, SKIP_NT, 4, 1, 3, false, false, false, true>(g, P, s)
+                    : launch_ssmm<true, true, 1, 1, 4, 1, 3, false, false, false, true>(g, P, s);
+  } else if (!variant) {
     if (gen)
       // One stored row tile per wave and matrix at every shape.  Large buckets: the gather needs
       // the registers.  Small and medium ones: two blocks then fit a CU, which doubles the weight
@@ -1770,6 +1864,9 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
                                : launch_ssmm2<false, true, 1, 4, 4, 1, 4>(d, P, s))
                       : (split ? launch_ssmm2<false, true, 1, 1, 4, 1, 4, 2, true>(d, P, s)
                                : launch_ssmm2<false, true, 1, 1, 4, 1, 4, 2>(d, P, s));
+  } else if (pl.skip) {
+    st = shape >= 1 ? launch_ssmm<false, true, 2, SKIP_NT, 4, 1, 3, false, false, false, true>(d, P, s)
+                    : launch_ssmm<false, true, 1, 1, 4, 1, 3, false, false, false, true>(d, P, s);
   } else if (gen) {
     if (split)
       st = shape == 1 ? launch_ssmm<false, false, 2, 2, 4, 1, 3, true, false, true>(d, P, s)

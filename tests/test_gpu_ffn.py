@@ -338,3 +338,26 @@ def test_seeded_sweep_matches_oracle(cfg, act, gated):
     print(f"  rel_fro={err:.3e} worst token={worst:.3e}", flush=True)
     assert err <= G.TOL, err
     assert worst <= 4 * G.TOL, worst
+
+
+# ---- Sub-Row compute skipping (sections 4.1, 4.3): one MFMA per stored operand into intermediate sums,
+# merged into the accumulators of the source rows at the end of every V-wide block ----
+SKIP_CASES = [
+    LayerConfig("skip32_small", T=20, H=256, F=384, E=4, topk=2, fmt=(1, 2, 32), seed=91),
+    LayerConfig("skip32_mid", T=300, H=256, F=448, E=4, topk=1, fmt=(1, 2, 32), seed=92),      # 14 stored row tiles: ragged rows too
+    LayerConfig("skip32_big_shared", T=700, H=256, F=384, E=4, topk=2, S=1, fmt=(1, 2, 32), renormalize=False, seed=93),
+    LayerConfig("skip64", T=333, H=384, F=512, E=6, topk=2, fmt=(1, 2, 64), seed=94),           # merge every second k block
+    LayerConfig("skip128", T=500, H=256, F=640, E=3, topk=2, fmt=(1, 2, 128), seed=95),         # a Sub-Row spans two stages
+    LayerConfig("skip96", T=200, H=192, F=384, E=4, topk=2, fmt=(1, 2, 96), seed=96),           # three k blocks: not a power of two
+]
+
+
+@pytest.mark.parametrize("cfg", SKIP_CASES, ids=[c.name for c in SKIP_CASES])
+def test_subrow_compute_skipping_matches_oracle(monkeypatch, tuning_library, cfg):
+    monkeypatch.setenv("SSMM_SUBROW_SKIP", "1")
+    got, ref, err = run_case(cfg)
+    monkeypatch.delenv("SSMM_SUBROW_SKIP")
+    y, _ = G.run_gpu_layer(cfg, *G.make_inputs(cfg))      # the masked scheme on the same inputs
+    d = G.rel_fro(G.bf16_tensor_to_f64(y), got)
+    print(f"  skipping vs masked rel_fro={d:.3e}", flush=True)
+    assert d <= G.TOL     # same products, another order of the fp32 sums
