@@ -96,7 +96,8 @@ int ssmm_compressed_sizes(int64_t rows, int64_t K, ssmm_format f, size_t* values
  * Prune and encode E dense matrices (section 4.1; pruning criterion: magnitude --
  * Sub-Rows ranked by the fp64 sum of squares of their V unpruned values, then the
  * two largest |v| of every group of 4; equal scores go to the lower row / lower
- * position).
+ * position; a NaN weight ranks like an infinity in both steps, so it is kept and stays
+ * visible in the outputs).
  *   w_dense  in   bf16 [E][rows][K]
  *   values   out  bf16 [E][rc][K/2]          canonical, may be NULL together with meta/index
  *   meta     out  u32  [E][rc][ceil(K/32)]   canonical
@@ -149,6 +150,10 @@ int ssmm_expand_tiled_weights(const void* tiled, int E, int64_t rows, int64_t K,
  * lower expert id first) in descending order, weight = softmax probability,
  * divided by the sum of the chosen ones when `renormalize` != 0.  Shared
  * experts have ids E..E+n_shared-1, weight 1, and take every token.
+ * A logit of -infinity masks an expert (weight 0); a NaN logit counts as -infinity.  When a
+ * token has fewer than `topk` logits above -infinity the rest of its choice goes by ascending
+ * expert id, so its ids are always distinct; a token without any logit above -infinity
+ * gets ids 0..topk-1 and weights that are not numbers.
  *   logits          in   f32 [T][E]
  *   topk_ids        out  i32 [T][topk]
  *   topk_w          out  f32 [T][topk]

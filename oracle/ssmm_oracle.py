@@ -42,7 +42,8 @@ import numpy as np
 def bf16_bits_to_f64(bits):
     """uint16 bf16 bit patterns -> float64 (exact)."""
     b = np.ascontiguousarray(bits, dtype=np.uint16)
-    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    with np.errstate(invalid="ignore"):   # signalling NaN patterns are legal inputs
+        return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
 
 
 def f64_to_bf16_bits(x):
@@ -116,13 +117,17 @@ def _kept_subrows(w, fmt):
     """For every block (M rows x V columns) the offsets of the N kept Sub-Rows,
     ascending.  Score = sum of squares of the V unpruned values, added in
     ascending column order in fp64; the N highest scores win, equal scores
-    going to the lower row.  Returns int array [rows/M][K/V][N]."""
+    going to the lower row.  A score that is not a number (a NaN weight, or
+    infinities of both signs... cannot occur: squares) ranks like +infinity: a
+    Sub-Row that holds a NaN is kept, so the NaN shows in the layer's output
+    instead of being pruned away.  Returns int array [rows/M][K/V][N]."""
     rows, K = w.shape
     M, V, N = fmt.M, fmt.V, fmt.N
     blk = w.reshape(rows // M, M, K // V, V)
     score = np.zeros(blk.shape[:3], dtype=np.float64)
     for v in range(V):
         score = score + blk[..., v] * blk[..., v]
+    score = np.where(np.isnan(score), np.inf, score)
     score = np.moveaxis(score, 1, 2)                       # [rows/M][K/V][M]
     order = np.argsort(-score, axis=-1, kind="stable")     # stable: lower row first on ties
     return np.sort(order[..., :N], axis=-1)
@@ -130,10 +135,12 @@ def _kept_subrows(w, fmt):
 
 def _kept_2of4(w):
     """For every group of 4 consecutive reduction elements the 2 positions kept:
-    the two largest |v|, equal magnitudes going to the lower position; returned
-    ascending.  Shape [rows][K/4][2]."""
+    the two largest |v|, equal magnitudes going to the lower position; a NaN
+    ranks like an infinity (it is kept and stays visible); returned ascending.
+    Shape [rows][K/4][2]."""
     rows, K = w.shape
     a = np.abs(w.reshape(rows, K // 4, 4))
+    a = np.where(np.isnan(a), np.inf, a)
     order = np.argsort(-a, axis=-1, kind="stable")
     return np.sort(order[..., :2], axis=-1)
 
@@ -243,6 +250,10 @@ def route(logits, topk, n_shared=0, renormalize=True):
     equal logits -> lower expert id) in descending-logit order; weight = p of
     each, divided by their sum when ``renormalize``.  Shared experts (section
     6.2) follow as ids E..E+S-1 with weight 1 in slots k..k+S-1.
+    A NaN logit counts as -infinity (a masked expert): it has weight 0 and is
+    chosen only when fewer than k logits are above -infinity, then in ascending
+    id order like any other tie.  A token without any logit above -infinity
+    has no defined weights (NaN); its ids are 0..k-1.
 
     Returns ids int32 [T][k+S], w float64 [T][k+S].
     """
@@ -251,7 +262,9 @@ def route(logits, topk, n_shared=0, renormalize=True):
     if not 1 <= topk <= E:
         raise ValueError("need 1 <= topk <= E")
     l64 = lg.astype(np.float64)
-    p = np.exp(l64 - l64.max(axis=1, keepdims=True))
+    l64 = np.where(np.isnan(l64), -np.inf, l64)
+    with np.errstate(invalid="ignore"):
+        p = np.exp(l64 - l64.max(axis=1, keepdims=True))
     p = p / p.sum(axis=1, keepdims=True)
     order = np.argsort(-l64, axis=1, kind="stable")[:, :topk]
     w = np.take_along_axis(p, order, axis=1)

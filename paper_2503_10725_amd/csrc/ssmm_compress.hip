@@ -34,6 +34,7 @@ __global__ void __launch_bounds__(256) select_subrows_kernel(const uint16_t* __r
         double x = bf16_to_f64(base[(int64_t)m * K + v]);
         score = score + x * x;
       }
+      if (score != score) score = __builtin_huge_val();   // a Sub-Row with a NaN ranks like +infinity: it is kept, the NaN stays visible
       if (best < 0 || score > best_score) {
         best = m;
         best_score = score;
@@ -51,10 +52,11 @@ __global__ void __launch_bounds__(256) select_subrows_kernel(const uint16_t* __r
 }
 
 // 2:4 choice on one group: the two largest magnitudes, ties to the lower position.
-// For finite bf16 the order of |v| is the order of the bit pattern without its sign.
+// The order of |v| is the order of the bf16 bit pattern without its sign; a NaN ranks like an
+// infinity (it is kept and stays visible in the outputs).
 __device__ inline void choose_2of4(const uint16_t v[4], int& p0, int& p1) {
   int m[4];
-  for (int i = 0; i < 4; i++) m[i] = v[i] & 0x7FFF;
+  for (int i = 0; i < 4; i++) m[i] = min(v[i] & 0x7FFF, 0x7F80);
   int first = 0;
   for (int i = 1; i < 4; i++)
     if (m[i] > m[first]) first = i;

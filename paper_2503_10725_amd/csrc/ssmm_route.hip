@@ -27,7 +27,10 @@ __device__ inline float wave_sum(float v) {
 }
 
 // Routing of token t by one wavefront.  Lane l owns experts l, l+64, l+128, l+192; lane j < topk
-// returns the j-th choice (expert id, weight).
+// returns the j-th choice (expert id, weight).  A NaN logit counts as -infinity (a masked expert):
+// weight 0, chosen only when fewer than topk logits are above -infinity, then by ascending id
+// like any other tie; the ids of a token are always distinct.
+__device__ inline float logit_or_minus_inf(float v) { return v != v ? -__builtin_huge_valf() : v; }
 __device__ inline void route_token(const float* __restrict__ logits, int t, int E, int topk, int renormalize, int lane,
                                    int& out_id, float& out_w) {
   const float NEG = -__builtin_huge_valf();
@@ -35,7 +38,7 @@ __device__ inline void route_token(const float* __restrict__ logits, int t, int 
     // One expert per lane: a lane's place in the descending order (ties: lower id first) is the
     // number of experts that beat it, counted against every lane's logit in turn (64 broadcasts,
     // no dependent cross-lane chain).
-    const float lg = lane < E ? logits[(int64_t)t * E + lane] : NEG;
+    const float lg = lane < E ? logit_or_minus_inf(logits[(int64_t)t * E + lane]) : NEG;
     int place = 0;
     float mx = NEG;
 #pragma unroll
@@ -67,7 +70,7 @@ __device__ inline void route_token(const float* __restrict__ logits, int t, int 
   float lg[4], pr[4];
   for (int i = 0; i < 4; i++) {
     const int e = lane + 64 * i;
-    lg[i] = e < E ? logits[(int64_t)t * E + e] : NEG;
+    lg[i] = e < E ? logit_or_minus_inf(logits[(int64_t)t * E + e]) : NEG;
   }
   const float mx = wave_max(fmaxf(fmaxf(lg[0], lg[1]), fmaxf(lg[2], lg[3])));
   float s = 0.f;
@@ -79,13 +82,20 @@ __device__ inline void route_token(const float* __restrict__ logits, int t, int 
   float my_w = 0.f;   // lane j keeps the j-th choice
   int my_id = 0;
   float chosen_sum = 0.f;
+  // bit i of `open`: expert lane + 64 i exists and has not been chosen yet (a chosen expert is
+  // struck out here, not by overwriting its logit: -infinity is a legal logit that may still be
+  // chosen, once, when fewer than topk experts are above it)
+  uint32_t open = 0;
+  for (int i = 0; i < 4; i++)
+    if (lane + 64 * i < E) open |= 1u << i;
+  const int kNone = 1 << 30;   // id of "no candidate": loses every tie
   for (int j = 0; j < topk; j++) {
-    // lane-local best (lower expert id first on equal logits), then across the wave
-    float bv = lg[0];
-    int bi = lane;
-    float bp = pr[0];
-    for (int i = 1; i < 4; i++)
-      if (lg[i] > bv) {
+    // lane-local best among the open experts (lower expert id first on equal logits), then across the wave
+    float bv = NEG;
+    int bi = kNone;
+    float bp = 0.f;
+    for (int i = 0; i < 4; i++)
+      if (((open >> i) & 1u) && (bi == kNone || lg[i] > bv)) {
         bv = lg[i];
         bi = lane + 64 * i;
         bp = pr[i];
@@ -107,7 +117,7 @@ __device__ inline void route_token(const float* __restrict__ logits, int t, int 
       my_id = bi;
     }
     for (int i = 0; i < 4; i++)
-      if (bi == lane + 64 * i) lg[i] = NEG;   // remove the winner
+      if (bi == lane + 64 * i) open &= ~(1u << i);   // strike the winner out
   }
   out_id = my_id;
   out_w = renormalize ? my_w / chosen_sum : my_w;

@@ -16,7 +16,11 @@ def random_bits(rng, shape, kind):
         f = rng.standard_normal(shape).astype(np.float32) * 0.02
     else:   # many exact ties, zeros and negative zeros
         f = rng.choice(np.array([0.0, -0.0, 0.5, -0.5, 1.0, -1.0, 2.0], dtype=np.float32), size=shape)
-    return (f.view(np.uint32) >> 16).astype(np.uint16)
+    bits = (f.view(np.uint32) >> 16).astype(np.uint16)
+    if kind == "non-finite":   # NaNs (several payloads, both signs) and infinities among the ties: a NaN ranks like an infinity
+        mask = rng.random(shape) < 0.05
+        bits[mask] = rng.choice(np.array([0x7FC0, 0xFFC0, 0x7FA1, 0x7F80, 0xFF80], dtype=np.uint16), size=int(mask.sum()))
+    return bits
 
 
 CASES = [
@@ -43,7 +47,7 @@ CASES = [
 
 
 @pytest.mark.parametrize("E,rows,K,fmt", CASES)
-@pytest.mark.parametrize("kind", ["normal", "ties"])
+@pytest.mark.parametrize("kind", ["normal", "ties", "non-finite"])
 def test_compress_decompress_untile_bit_exact(E, rows, K, fmt, kind):
     print(f"case E={E} rows={rows} K={K} fmt={fmt} kind={kind}", flush=True)
     rng = np.random.default_rng(E * 1000 + rows + K + len(kind))

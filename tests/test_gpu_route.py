@@ -128,3 +128,23 @@ def test_router_logits_argument_checks():
         B.router_logits(x, wr)
     assert B.router_logits(torch.zeros((0, 32), dtype=torch.bfloat16, device="cuda"),
                            torch.zeros((4, 32), dtype=torch.bfloat16, device="cuda")).shape == (0, 4)
+
+
+@pytest.mark.parametrize("E,topk", [(8, 2), (130, 4), (64, 8), (250, 16)])
+def test_masked_and_nan_logits_give_distinct_ids(E, topk):
+    """-infinity logits (masked experts) and NaN logits (counted as -infinity): when a token has fewer
+    than topk numbers among its logits the rest of its choice goes by ascending expert id, and its ids
+    stay distinct (every bucket position is written).  Bit-exact against the oracle, on both routing
+    paths (up to 64 experts: ranks by place; above: repeated arg-max)."""
+    rng = np.random.default_rng(E + topk)
+    lg = rng.standard_normal((600, E)).astype(np.float32)
+    lg[:, ::3] = -np.inf
+    lg[5:90, 1::3] = np.nan
+    lg[100:200] = -np.inf
+    lg[100:200, [E - 1, 2]] = [0.5, -1.0]        # two numbers per token only
+    lg[300:350] = np.nan
+    lg[300:350, E // 2] = 3.0                    # one number per token only
+    r = check(lg, topk, 1, True)
+    ids = r.topk_ids.cpu().numpy()
+    assert all(len(set(row)) == topk for row in ids.tolist())
+    assert (ids[100:200, :2] == [E - 1, 2]).all() and (ids[300:350, 0] == E // 2).all()

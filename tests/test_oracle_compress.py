@@ -6,6 +6,8 @@ reference below is written with plain Python loops and Python floats.
 import os
 
 import numpy as np
+import math
+
 import pytest
 
 from oracle import ssmm_oracle as O
@@ -46,7 +48,7 @@ def brute_prune(bits, N, M, V):
                     for v in range(V):
                         x = val[b * M + m][s * V + v]
                         acc = acc + x * x
-                    scores.append(acc)
+                    scores.append(math.inf if math.isnan(acc) else acc)   # a NaN ranks like +infinity
                 chosen = []
                 for _ in range(N):
                     best = None
@@ -65,7 +67,7 @@ def brute_prune(bits, N, M, V):
         for g in range(K // 4):
             if not live[r][4 * g]:
                 continue
-            mags = [abs(val[r][4 * g + i]) for i in range(4)]
+            mags = [math.inf if math.isnan(val[r][4 * g + i]) else abs(val[r][4 * g + i]) for i in range(4)]
             first = max(range(4), key=lambda i: (mags[i], -i))
             second = max((i for i in range(4) if i != first), key=lambda i: (mags[i], -i))
             for i in (first, second):
@@ -95,7 +97,7 @@ def load_golden(name):
     return data
 
 
-@pytest.mark.parametrize("name", ["two_four_worked.txt", "subrow_worked.txt"])
+@pytest.mark.parametrize("name", ["two_four_worked.txt", "subrow_worked.txt", "subrow_2of4_worked.txt"])
 def test_hand_worked_examples(name):
     g = load_golden(name)
     dense = np.array(g["dense"], dtype=np.uint16)
@@ -116,6 +118,39 @@ def test_hand_worked_examples(name):
 # ---------------------------------------------------------------- brute force on small inputs
 
 FORMATS = [(1, 1, 0), (1, 2, 8), (1, 2, 4), (2, 4, 8), (4, 8, 32), (1, 2, 16), (3, 4, 4)]
+
+
+def plant_non_finite(rng, bits, share=0.05):
+    """NaNs (two payloads, both signs) and infinities scattered over a bf16 matrix."""
+    bits = bits.copy()
+    special = np.array([0x7FC0, 0xFFC0, 0x7FA1, 0x7F80, 0xFF80], dtype=np.uint16)
+    mask = rng.random(bits.shape) < share
+    bits[mask] = rng.choice(special, size=int(mask.sum()))
+    return bits
+
+
+@pytest.mark.parametrize("fmt", FORMATS)
+def test_not_a_number_ranks_like_infinity_and_is_kept(fmt):
+    """The paper says nothing of NaN or infinite weights; the rule here: a NaN ranks like an infinity
+    in both prunings (a Sub-Row that holds one, and the value itself in its group of 4), ties as
+    always to the lower row / position.  Brute force with the rule spelled out, and the encoding
+    still round-trips bit for bit (NaN payloads included)."""
+    rng = np.random.default_rng(7000 + 100 * fmt[1] + fmt[2])
+    f = O.Format(*fmt)
+    V = max(fmt[2], 4)
+    rows, K = 2 * fmt[1] * 3, V * 3 if V % 8 == 0 else V * 6
+    bits = plant_non_finite(rng, random_bf16(rng, (rows, K), "ties"))
+    pruned = O.prune(bits, f)
+    np.testing.assert_array_equal(pruned, brute_prune(bits, *fmt))
+    values, meta, index = O.compress(bits, f)
+    np.testing.assert_array_equal(O.decompress(values, meta, index, rows, K, f), pruned)
+    # a group of a kept Sub-Row never drops a NaN in favour of a number
+    val = O.bf16_bits_to_f64(bits).reshape(rows, K // 4, 4)
+    kept = (pruned.reshape(rows, K // 4, 4) != 0) | (bits.reshape(rows, K // 4, 4) == 0)
+    if fmt[0] == fmt[1]:
+        for r, g in zip(*np.nonzero(np.isnan(val).any(axis=2))):
+            n_nan = int(np.isnan(val[r, g]).sum())
+            assert int((np.isnan(val[r, g]) & (pruned.reshape(rows, K // 4, 4)[r, g] != 0)).sum()) == min(n_nan, 2)
 
 
 @pytest.mark.parametrize("fmt", FORMATS)

@@ -13,7 +13,7 @@ def brute_route(logits, k, renorm):
     (first maximum wins, i.e. the lower expert id on equal logits)."""
     ids, ws = [], []
     for row in logits:
-        row = [float(v) for v in row]
+        row = [-math.inf if math.isnan(float(v)) else float(v) for v in row]   # a NaN logit counts as -infinity
         mx = max(row)
         ex = [math.exp(v - mx) for v in row]
         tot = sum(ex)
@@ -48,6 +48,30 @@ def test_route_matches_brute_force(E, k, renorm):
     assert ids.tolist() == bids
     np.testing.assert_allclose(w, np.array(bw), rtol=1e-13, atol=0)
     assert ids[3].tolist() == list(range(k))
+
+
+@pytest.mark.parametrize("E,k", [(8, 2), (130, 4), (64, 8), (200, 16)])
+def test_masked_and_nan_logits(E, k):
+    """Logits of -infinity (masked experts) and NaN (counted as -infinity): weight 0, never preferred to a
+    number, and when fewer than k logits are numbers the rest of the choice goes by ascending id --
+    ids stay distinct.  Brute force with the rule spelled out."""
+    rng = np.random.default_rng(E + k)
+    lg = rng.standard_normal((40, E)).astype(np.float32)
+    lg[:, ::3] = -np.inf
+    lg[5:9, 1::3] = np.nan
+    lg[10] = -np.inf
+    lg[10, [E - 1, 2]] = [0.5, -1.0]          # two numbers only: fewer than k for every k here but 2
+    lg[11] = np.nan
+    lg[11, E // 2] = 3.0                      # one number only
+    for renorm in (True, False):
+        with np.errstate(invalid="ignore", divide="ignore"):
+            ids, w = O.route(lg, k, 0, renorm)
+        bids, bw = brute_route(lg, k, renorm)
+        assert ids.tolist() == bids
+        np.testing.assert_allclose(w, np.array(bw), rtol=1e-13, atol=0)
+        assert all(len(set(r)) == k for r in ids.tolist())
+    assert ids[10, :2].tolist() == [E - 1, 2] and ids[10, 2:].tolist() == [e for e in range(E) if e not in (E - 1, 2)][: k - 2]
+    assert ids[11, 0] == E // 2 and w[11, 0] == 1.0 and (w[11, 1:] == 0).all()
 
 
 def test_route_closed_forms():
