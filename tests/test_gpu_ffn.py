@@ -361,3 +361,22 @@ def test_subrow_compute_skipping_matches_oracle(monkeypatch, tuning_library, cfg
     d = G.rel_fro(G.bf16_tensor_to_f64(y), got)
     print(f"  skipping vs masked rel_fro={d:.3e}", flush=True)
     assert d <= G.TOL     # same products, another order of the fp32 sums
+
+
+@pytest.mark.parametrize("fmt", [(1, 1, 0), (1, 2, 8), (4, 8, 32)], ids=["2:4", "1:2:8", "4:8:32"])
+def test_extreme_bucket_skew(fmt):
+    """One expert with a single token, one with more than a thousand (several full token tiles and a ragged one),
+    one with a few dozen, one with none: every tile shape meets every kind of ragged end in one layer (the tile
+    rules only see the mean bucket)."""
+    cfg = LayerConfig("skew", T=1300, H=256, F=384, E=4, topk=1, fmt=fmt, seed=97)
+
+    def mutate(x, lg, wg, wu, wd):
+        lg = torch.full_like(lg, -4.0)
+        lg[:, 1] = 4.0                 # nearly everybody goes to expert 1
+        lg[0, 0] = 8.0                 # token 0 alone on expert 0
+        lg[100:137, 2] = 8.0           # 37 tokens on expert 2, none on expert 3
+        return x, lg, wg, wu, wd
+
+    _, ref, _ = run_case(cfg, mutate=mutate)
+    counts = np.diff(ref["offsets"])
+    assert counts.tolist() == [1, 1300 - 38, 37, 0]
