@@ -394,8 +394,9 @@ WORKLOADS = {
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50,
+                    help="untimed steps before the timed ones; the first ~25 steps after idle run 5-10 %% slower (clock ramp)")
     ap.add_argument("--tokens", type=int, default=None, help="token count of the headline point (default: the layer's own, 4096 for the headline layer)")
     ap.add_argument("--config", default="mixtral", help="layer of synth.CONFIGS to time as the headline (default: the Mixtral-shaped one)")
     ap.add_argument("--format", default=None, metavar="N,M,V",

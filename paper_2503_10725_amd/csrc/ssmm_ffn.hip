@@ -1428,6 +1428,7 @@ inline int64_t resident_grid(int64_t tiles_bound, int occ, const DeviceShape& de
   const int64_t resident = (int64_t)dev.cus * occ / kXcdGroups * kXcdGroups;
   const int persistent = knob("SSMM_PERSISTENT");   // 0: one block per tile
   if (persistent != 0 && grid > resident) grid = resident;
+  if (const int want = knob("SSMM_GRID"); want > 0 && want % kXcdGroups == 0 && grid > want) grid = want;   // smaller resident set
   return grid;
 }
 
