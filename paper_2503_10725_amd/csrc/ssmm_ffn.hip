@@ -499,31 +499,58 @@ __global__ void __launch_bounds__(64 * WM * WN) ssmm_kernel(const SsmmArgs p) {
   // from the tiles that exist, so that all eight get an equal share (with the ranges cut from the
   // grid the last XCDs got only blocks without a tile, and the first ones a second round).
   const int MTB = (p.row_tiles + MT * WM - 1) / (MT * WM) * (SPLITK ? p.ksplit : 1);
+  // Buckets are looked at 64 at a time, one per lane (their offsets load side by side: one memory
+  // latency per 64 buckets instead of one per bucket), tile counts summed by a wave scan; every wave
+  // does the same work and arrives at the same, wave-uniform, answer.
+  const int ln = threadIdx.x & 63;
+  auto scan64 = [&](int base, int& lo, int& tok_tiles, int& tiles) {   // returns the inclusive sum of `tiles` over the lanes
+    const int i = base + ln;
+    lo = bucket_offset(p, min(i, p.E_total));
+    const int hi = bucket_offset(p, min(i + 1, p.E_total));
+    tok_tiles = (hi - lo + NB - 1) / NB;
+    tiles = i < p.E_total ? tok_tiles * MTB : 0;
+    int incl = tiles;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int below = __shfl_up(incl, d, 64);
+      if (ln >= d) incl += below;
+    }
+    return incl;
+  };
   int total = 0;
-  for (int i = 0; i < p.E_total; i++) total += (bucket_offset(p, i + 1) - bucket_offset(p, i) + NB - 1) / NB * MTB;
+  for (int base = 0; base < p.E_total; base += 64) {
+    int lo, tok_tiles, tiles;
+    total += __shfl(scan64(base, lo, tok_tiles, tiles), 63, 64);
+  }
+  total = __builtin_amdgcn_readfirstlane(total);
   constexpr int nx = kXcdGroups;
   const int per_xcd = (total + nx - 1) / nx;
   if ((int)(blockIdx.x / nx) >= per_xcd) return;   // uniform over the block
   const int L = (blockIdx.x % nx) * per_xcd + blockIdx.x / nx;
   int e = -1, row0 = 0, nvalid = 0, mtb = 0, split = 0;
   {
-    int before = 0;   // blocks of the experts before i
-    for (int i = 0; i < p.E_total; i++) {
-      const int lo = bucket_offset(p, i), hi = bucket_offset(p, i + 1);
-      const int tiles = (hi - lo + NB - 1) / NB;
-      if (L < before + tiles * MTB) {
-        const int local = L - before;
-        e = i;
-        mtb = local / tiles;
+    int carry = 0;   // tiles of the buckets before this round's
+    for (int base = 0; base < p.E_total && e < 0; base += 64) {
+      int lo, tok_tiles, tiles;
+      const int incl = scan64(base, lo, tok_tiles, tiles);
+      const int before = carry + incl - tiles;
+      const uint64_t hit = __ballot(tiles > 0 && before <= L && L < before + tiles);
+      if (hit) {
+        const int src = __ffsll((unsigned long long)hit) - 1;
+        const int lo_e = __builtin_amdgcn_readfirstlane(__shfl(lo, src, 64));
+        const int tt_e = __builtin_amdgcn_readfirstlane(__shfl(tok_tiles, src, 64));
+        const int local = L - __builtin_amdgcn_readfirstlane(__shfl(before, src, 64));
+        const int hi_e = __builtin_amdgcn_readfirstlane(bucket_offset(p, base + src + 1));
+        e = base + src;
+        mtb = local / tt_e;
         if (SPLITK) {
           split = mtb % p.ksplit;
           mtb /= p.ksplit;
         }
-        row0 = lo + (local % tiles) * NB;
-        nvalid = min(NB, hi - row0);
-        break;
+        row0 = lo_e + (local % tt_e) * NB;
+        nvalid = min(NB, hi_e - row0);
       }
-      before += tiles * MTB;
+      carry += __builtin_amdgcn_readfirstlane(__shfl(incl, 63, 64));
     }
   }
   if (e < 0) return;   // uniform over the block: beyond the last tile
@@ -1032,13 +1059,26 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) ssmm_kernel2(const SsmmArgs
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wv % WM, wn = wv / WM;
   const int MTB = (p.row_tiles + MT * WM - 1) / (MT * WM) * (SPLITK ? p.ksplit : 1);
-  if (tid == 0) {
-    int c = 0;
-    for (int i = 0; i <= p.E_total; i++) {
-      const int lo = bucket_offset(p, i);
-      tab_cum[i] = c;
-      tab_off[i] = lo;
-      if (i < p.E_total) c += (bucket_offset(p, i + 1) - lo + NB - 1) / NB * MTB;
+  // Tile table, built by the first wave: 64 buckets per round, their offsets loaded side by side
+  // (one memory latency per round instead of one per bucket), tile counts summed by a wave scan.
+  if (wv == 0) {
+    int carry = 0;
+    for (int base = 0; base <= p.E_total; base += 64) {
+      const int i = base + lane;
+      const int lo = bucket_offset(p, min(i, p.E_total));
+      const int hi = bucket_offset(p, min(i + 1, p.E_total));
+      const int tiles = i < p.E_total ? (hi - lo + NB - 1) / NB * MTB : 0;
+      int incl = tiles;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int below = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += below;
+      }
+      if (i <= p.E_total) {
+        tab_cum[i] = carry + incl - tiles;
+        tab_off[i] = lo;
+      }
+      carry += __shfl(incl, 63, 64);
     }
   }
   __syncthreads();
