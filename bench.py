@@ -88,6 +88,17 @@ def sustained_mfma_share():
         return None
 
 
+def sustained_hbm_share():
+    """Share of the published HBM bandwidth that a kernel which only reads sustains on this chip: the best row
+    of the committed table of `bench.py --hbm-probe` (None if absent)."""
+    path = os.path.join(ROOT, "profiles", "hbm_stream_rate.txt")
+    try:
+        vals = [float(line.split("|")[5]) for line in open(path) if not line.startswith("#") and line.count("|") == 5]
+        return max(vals) if vals else None
+    except (OSError, ValueError, IndexError):
+        return None
+
+
 def run_point(cfg, enc, steps, warmup, B, synth, torch):
     """Time `steps` passes of the hot path at cfg.T tokens.  Returns a dict of measurements."""
     dev = "cuda"
@@ -193,7 +204,47 @@ def probe_library():
     lib.ssmm_probe_mfma.restype = ctypes.c_int
     lib.ssmm_probe_mfma.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                     ctypes.c_void_p, ctypes.POINTER(ctypes.c_float), ctypes.c_void_p]
+    lib.ssmm_probe_hbm_read.restype = ctypes.c_int
+    lib.ssmm_probe_hbm_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                        ctypes.POINTER(ctypes.c_float), ctypes.c_void_p]
     return lib
+
+
+def hbm_probe(torch, out_path=None, gib=8):
+    """What a kernel that only reads reaches: streaming read of a buffer far larger than the memory-side cache,
+    by blocks per compute unit and 16-byte loads in flight per thread.  The roof the small-token SSMM kernels
+    (which read their weights once) are read against is the published 8 TB/s; this table says how much of it
+    the memory system gives to any kernel.  Returns rows."""
+    import ctypes
+    lib = probe_library()
+    nbytes = gib << 30
+    buf = torch.empty((nbytes,), dtype=torch.uint8, device="cuda")
+    buf.view(torch.int32).random_()
+    sink = torch.zeros((4,), dtype=torch.int32, device="cuda")
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    rows = []
+    for rep in range(2):
+        for blocks_per_cu in (1, 2, 4, 8):
+            for in_flight in (1, 2, 4, 8):
+                ms = ctypes.c_float(0.0)
+                st = lib.ssmm_probe_hbm_read(ctypes.c_void_p(buf.data_ptr()), nbytes, blocks_per_cu, in_flight,
+                                             ctypes.c_void_p(sink.data_ptr()), ctypes.byref(ms), stream)
+                if st != 0:
+                    raise RuntimeError(f"ssmm_probe_hbm_read: status {st}")
+                span = in_flight * 256 * 16
+                read = nbytes // span * span
+                rows.append({"blocks_per_cu": blocks_per_cu, "loads_in_flight": in_flight, "repeat": rep, "ms": ms.value,
+                             "GBs": read / ms.value * 1e-6, "share_of_published_peak": read / ms.value * 1e-6 / HBM_PEAK_GBS})
+    if out_path:
+        with open(out_path, "w") as f:
+            f.write("# streaming read of %d GiB of device memory (memory-side cache: 256 MB), one MI355X\n" % gib)
+            f.write("# command: python3 bench.py --hbm-probe <this file>\n")
+            f.write("# blocks of 256 threads per compute unit | 16-byte loads in flight per thread | repeat | ms | GB/s | share of the published 8000 GB/s\n")
+            for r in rows:
+                f.write("%d | %d | %d | %7.3f | %7.1f | %.3f\n" % (r["blocks_per_cu"], r["loads_in_flight"], r["repeat"], r["ms"],
+                                                                r["GBs"], r["share_of_published_peak"]))
+    return rows
 
 
 def mfma_probe(torch, out_path=None):
@@ -373,6 +424,12 @@ def kernel_rooflines(cfg, pt, config_name):
              "avg_launch_ms": ms, "executed_TFLOPs": tf, "frac_mfma": tf / MFMA_BF16_PEAK_TFLOPS,
              "algorithmic_GBs": gbs, "frac_hbm": gbs / HBM_PEAK_GBS,
              "traffic": measured_traffic("gate_up" if key == "roofline" else "down", cfg.T, config_name)}
+        # context, not the peak: what back-to-back sparse MFMAs on random operands / a kernel that only reads sustain here
+        share = sustained_mfma_share() if mfma_bound else sustained_hbm_share()
+        if share:
+            r["sustained"] = {"share_of_peak": share, "frac_of_sustained": r["frac"] / share,
+                              "source": "profiles/sparse_mfma_rate_by_operand_bits.txt (bench.py --mfma-probe)" if mfma_bound
+                              else "profiles/hbm_stream_rate.txt (bench.py --hbm-probe)"}
         out[key] = r
     out["combine_GBs"] = cb_b / (pt["kernel_ms"]["combine"] * 1e-3) / 1e9
     return out
@@ -412,6 +469,9 @@ def main():
     ap.add_argument("--mfma-probe", metavar="FILE", default=None,
                     help="instead of the layer benchmark: time back-to-back matrix instructions (the kernels' sparse MFMA by "
                          "operand bits, the other sparse shape, the dense MFMA), write the table to FILE")
+    ap.add_argument("--hbm-probe", metavar="FILE", default=None,
+                    help="instead of the layer benchmark: streaming-read rate of the device memory (8 GiB buffer) by blocks "
+                         "per compute unit and loads in flight, write the table to FILE")
     ap.add_argument("--subrow-ab", metavar="FILE", default=None,
                     help="instead of the layer benchmark: Sub-Row compute skipping against the masked scheme for (1,2,V), "
                          "V = 32..1024, on the Mixtral shape; write the table to FILE")
@@ -433,6 +493,10 @@ def main():
     if args.mfma_probe:
         rows = mfma_probe(torch, args.mfma_probe)
         print(json.dumps({"metric": "sustained matrix-instruction rate by instruction and operand bits", "rows": rows}))
+        return
+    if args.hbm_probe:
+        rows = hbm_probe(torch, args.hbm_probe)
+        print(json.dumps({"metric": "streaming-read rate of the device memory, GB/s", "rows": rows}))
         return
     if args.subrow_ab:
         rows = subrow_ab(torch, B, synth, args.steps, args.warmup, args.subrow_ab)
@@ -479,10 +543,6 @@ def main():
     roofline = rl["roofline"]
     roofline["flops"] = "executed on the kept half of the weights (dense-equivalent = 2x)"
     roofline["traffic_unit"] = "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated; profiles/)"
-    share = sustained_mfma_share()
-    if share and roofline["bound"] == "mfma":   # context, not the peak: what the matrix pipes sustain on random operands at this chip's power limit
-        roofline["sustained"] = {"share_of_peak": share, "frac_of_sustained": roofline["frac"] / share,
-                                 "source": "profiles/sparse_mfma_rate_by_operand_bits.txt (bench.py --mfma-probe)"}
     roofline["combine_GBs"] = rl["combine_GBs"]
 
     sweep = []

@@ -5,7 +5,7 @@
                                                                rules read override knobs from the environment (tests
                                                                that force a code path, sweeps on the device; never
                                                                what a user of the library loads)
-                                             libssmm_probe.so  bench-only MFMA rate probe
+                                             libssmm_probe.so  bench-only probes (MFMA rate, HBM streaming rate)
 
 Every build of the library also compiles the SSMM kernels to device assembly and checks it: no SSMM
 kernel may use scratch memory, no hand-scheduled kernel may hold more accumulation registers than its
@@ -110,9 +110,9 @@ def build(verbose=True, extra=(), out=LIB):
 
 
 def build_probe(verbose=True):
-    """The MFMA rate probe: a library of its own that only bench.py loads."""
-    src = os.path.join(PKG, "csrc", "probe", "mfma_probe.hip")
-    cmd = [hipcc(), *HIPCC_FLAGS, "-shared", "-I", os.path.join(PKG, "csrc", "probe"), src, "-o", PROBE_LIB]
+    """The MFMA rate and HBM streaming probes: a library of its own that only bench.py loads."""
+    srcs = sorted(glob.glob(os.path.join(PKG, "csrc", "probe", "*.hip")))
+    cmd = [hipcc(), *HIPCC_FLAGS, "-shared", "-I", os.path.join(PKG, "csrc", "probe"), *srcs, "-o", PROBE_LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     rc, out = run(cmd)

@@ -33,6 +33,18 @@ size_t ssmm_probe_operand_bytes(void);
 int ssmm_probe_mfma(const void* operands, size_t operand_bytes, int iters, int idle_slots, int kind, float* sink,
                     float* ms_out, void* stream);
 
+/*
+ * Streaming read of `bytes` (>= 1 MiB, 16-byte aligned) of device memory by blocks_per_cu (1..8) blocks of
+ * 256 threads per compute unit, each thread with in_flight (1, 2, 4 or 8) 16-byte loads outstanding; one
+ * untimed pass, then one timed.  A buffer far larger than the 256 MB memory-side cache measures HBM.
+ *   sink    out  device, 16 bytes (never written in practice; keeps the loads alive)
+ *   ms_out  out  host: duration of the timed pass in milliseconds (bytes actually read: the largest multiple
+ *                of in_flight * 4096 bytes that fits)
+ * Synchronises the stream.  Returns 0, -1 (argument) or -4 (HIP).
+ */
+int ssmm_probe_hbm_read(const void* buf, size_t bytes, int blocks_per_cu, int in_flight, void* sink, float* ms_out,
+                        void* stream);
+
 #ifdef __cplusplus
 }
 #endif

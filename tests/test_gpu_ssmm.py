@@ -137,3 +137,31 @@ def test_mfma_probe_runs_and_reports_plausible_rates():
     assert run(buf[:64], 0, 0)[0] == -3
     assert run(buf, 3, 0)[0] == -1
     assert run(buf, 0, 5)[0] == -1
+
+
+def test_hbm_probe_reads_no_faster_than_the_memory_can():
+    """The other measurement aid of libssmm_probe.so: a streaming read of 1 GiB (four times the memory-side
+    cache) cannot beat the published 8 TB/s, and with eight blocks per compute unit and eight loads in flight
+    it reaches a good part of it; bad arguments are refused."""
+    import ctypes
+    import os
+    import sys
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import bench
+    lib = bench.probe_library()
+    nbytes = 1 << 30
+    buf = torch.empty((nbytes,), dtype=torch.uint8, device="cuda")
+    buf.view(torch.int32).random_()
+    sink = torch.zeros((4,), dtype=torch.int32, device="cuda")
+
+    def run(n, blocks, in_flight):
+        ms = ctypes.c_float(0.0)
+        st = lib.ssmm_probe_hbm_read(ctypes.c_void_p(buf.data_ptr()), n, blocks, in_flight, ctypes.c_void_p(sink.data_ptr()),
+                                     ctypes.byref(ms), None)
+        return st, (n / ms.value * 1e-6 if ms.value > 0 else 0.0)
+
+    st, gbs = run(nbytes, 8, 8)
+    print(f"streaming read: {gbs:.0f} GB/s", flush=True)
+    assert st == 0 and 2000.0 < gbs < 8000.0
+    assert not sink.bool().any()
+    assert run(nbytes, 0, 8)[0] == -1 and run(nbytes, 8, 3)[0] == -1 and run(1000, 8, 8)[0] == -1
