@@ -383,12 +383,16 @@ def test_extreme_bucket_skew(fmt):
 
 
 @pytest.mark.parametrize("fmt", [(1, 1, 0), (1, 2, 8), (4, 8, 32)], ids=["2:4", "1:2:8", "4:8:32"])
-@pytest.mark.parametrize("T", [40, 1500])
-def test_buckets_span_several_rounds_of_the_tile_table(fmt, T):
-    """200 routed experts + 1 shared: the kernels read the bucket offsets 64 at a time, so their tile table takes
-    four rounds, the last one with 10 buckets; at 40 tokens most buckets are empty, at 1500 the non-empty ones fill more than two rounds."""
-    cfg = LayerConfig("wide_table", T=T, H=128, F=128, E=200, topk=4, S=1, fmt=fmt, logits="biased", seed=131 + T)
+@pytest.mark.parametrize("T,E", [(40, 200), (1500, 200), (700, 255)])
+def test_buckets_span_several_rounds_of_the_tile_table(fmt, T, E):
+    """200 or 255 routed experts + 1 shared (256 buckets: the most route + bucket serve): the kernels read the bucket
+    offsets 64 at a time, so their tile table takes four rounds, the last one with few buckets or exactly full; at 40
+    tokens most buckets are empty, at 1500 the non-empty ones fill more than two rounds."""
+    cfg = LayerConfig("wide_table", T=T, H=128, F=128, E=E, topk=4, S=1, fmt=fmt, logits="biased", seed=131 + T)
     _, ref, _ = run_case(cfg)
     counts = np.diff(ref["offsets"])
-    assert len(counts) == 201 and counts[-1] == T
-    assert (counts == 0).any() if T == 40 else (counts > 0).sum() > 128
+    assert len(counts) == E + 1 and counts[-1] == T
+    if T == 40:
+        assert (counts == 0).any()
+    elif T == 1500:
+        assert (counts > 0).sum() > 128
