@@ -396,3 +396,32 @@ def test_buckets_span_several_rounds_of_the_tile_table(fmt, T, E):
         assert (counts == 0).any()
     elif T == 1500:
         assert (counts > 0).sum() > 128
+
+
+# ---- the same kind of sweep with many experts: bucket counts on both sides of 64, 128 and 192 (the kernels look at
+# ---- 64 buckets at a time), shared experts, from one token to a few thousand ----
+def _many_expert_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    fmts = [(1, 1, 0), (1, 2, 8), (4, 8, 32), (1, 1, 0), (8, 16, 32)]
+    cases = []
+    for i in range(n):
+        E = int(rng.choice([33, 63, 64, 65, 100, 127, 128, 129, 190, 250]))
+        topk = int(rng.integers(1, 9))
+        cfg = LayerConfig(f"experts{i}", T=int(rng.choice([1, 5, 17, 64, 200, 257, 900, 2500])), H=int(rng.integers(1, 5)) * 128,
+                          F=int(rng.integers(1, 5)) * 128, E=E, topk=topk, S=int(rng.integers(0, 3)), fmt=fmts[i % 5],
+                          logits=["normal", "biased"][i % 2], renormalize=bool(i % 3), seed=2000 + i)
+        act, gated = [("silu", True), ("gelu_tanh", True), ("relu", False), ("silu", True), ("silu", False)][(i // 5) % 5]
+        cases.append((cfg, act, gated))
+    return cases
+
+
+@pytest.mark.parametrize("cfg,act,gated", _many_expert_cases(20, 20250311), ids=lambda v: getattr(v, "name", str(v)))
+def test_seeded_sweep_with_many_experts_matches_oracle(cfg, act, gated):
+    print(f"case {cfg} activation={act} gated={gated}", flush=True)
+    x, lg, wg, wu, wd = G.make_inputs(cfg)
+    y, route = G.run_gpu_layer(cfg, x, lg, wg, wu, wd, activation=act, gated=gated)
+    ref = G.run_oracle_layer(cfg, x, lg, wg, wu, wd, act=act, gated=gated)
+    G.check_routing(route, ref, cfg)
+    err = G.rel_fro(G.bf16_tensor_to_f64(y), ref["y"])
+    print(f"  rel_fro={err:.3e}", flush=True)
+    assert err <= G.TOL, err
