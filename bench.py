@@ -345,7 +345,7 @@ def subrow_ab(torch, B, synth, steps, warmup, out_path=None, tokens=4096):
     if out_path:
         with open(out_path, "w") as f:
             f.write("# Sub-Row compute skipping against the masked scheme: Mixtral-shaped layer (H 4096, F 14336, 8 experts top-2), %d tokens, (1,2,V)+2:4 weights, one MI355X\n" % tokens)
-            f.write("# command: python3 bench.py --subrow-ab <this file>\n")
+            f.write("# command: python3 bench.py --steps %d --warmup %d --subrow-ab <this file>\n" % (steps, warmup))
             f.write("# whole step (route .. combine) and its two SSMM kernels from HIP events; mean of %d steps\n" % steps)
             f.write("# V | variant | ms per step | gate/up ms | down ms | dense-equiv TFLOP/s\n")
             for r in rows:

@@ -976,6 +976,17 @@ struct SsmmPipe {
     vxo = lane2;
     prologue<-(DS - 1)>(KS);
   }
+  // The lane's offsets into the A streams, from the lane number, as they stand after start(): computed again
+  // behind the epilogue so that they hold no registers while it runs.
+  __device__ inline void refresh_offsets(int lane) {
+    lane16 = lane * 16;
+    lane4 = lane * 4;
+    lane2 = lane * 2;
+    asm volatile("" : "+v"(lane16), "+v"(lane4), "+v"(lane2));
+    va = lane16 + ((uint32_t)sa << 11);
+    vm = lane4 + ((uint32_t)sa << 8);
+    if (VEC) vxo = lane2 + ((uint32_t)sa << 7);
+  }
   // Cleared while the first stages are on their way: one dense MFMA 0 x 0 + 0 per accumulator tile
   // (output-only for the compiler: no zero tile to keep in, or spill from, registers).
   __device__ inline void clear() {
@@ -1137,14 +1148,15 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) ssmm_kernel2(const SsmmArgs
   t.dma_w = __builtin_amdgcn_readfirstlane(lds_address(lds) + wv * 1024);
   // operand reads: lane (j, ph) reads pieces 2ph, 2ph+1 (k block 0) and 4+2ph, 5+2ph (k block 1)
   // of row j of each of its token tiles
-  {
-    const int j = lane & 31, ph = lane >> 5, swz = j & 7;   // (row & 7) == (j & 7): token tiles start at multiples of 32
+  auto operand_offsets = [&](int l) {
+    const int j = l & 31, ph = l >> 5, swz = j & 7;   // (row & 7) == (j & 7): token tiles start at multiples of 32
     const uint32_t rowb = (uint32_t)((wn * NT * 32 + j) * 128);
     t.rd[0] = rowb + (((2 * ph) ^ swz) << 4);
     t.rd[1] = rowb + (((2 * ph + 1) ^ swz) << 4);
     t.rd[2] = rowb + (((4 + 2 * ph) ^ swz) << 4);
     t.rd[3] = rowb + (((5 + 2 * ph) ^ swz) << 4);
-  }
+  };
+  operand_offsets(lane);
 
   const uint32_t sel_w0 = __builtin_amdgcn_readfirstlane(lds_address(side_sel) + wv * 256);
   const uint32_t w_w0 = __builtin_amdgcn_readfirstlane(lds_address(side_w) + wv * 256);
@@ -1176,6 +1188,19 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) ssmm_kernel2(const SsmmArgs
   };
 
   Where cur = {}, prev = {};
+  // per-lane offsets of the token-tile transfers of tile cur (rel: counted from the tile's first row)
+  auto transfer_offsets = [&](bool rel) {
+    int src[CH];
+    rows_of(cur, src);
+#pragma unroll
+    for (int i = 0; i < CH; i++) {
+      const int slot = i * NTH + wv * 64 + ln, r = slot >> 3, c = (slot & 7) ^ (r & 7);
+      const int row = rel ? min(r, cur.nvalid - 1) : src[i];
+      t.vb[i] = (uint32_t)(((int64_t)row * p.K + c * 8) * 2);
+    }
+#pragma unroll
+    for (int i = 0; i < CH; i++) asm volatile("" : "+v"(t.vb[i]));   // as computed here, not carried over from the first time
+  };
   int parity = 0;   // of the tile the accumulators belong to when the epilogue runs
   // epilogue of the tile whose sums the accumulators hold: see ssmm_kernel
   auto epilogue = [&]() {
@@ -1207,13 +1232,19 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) ssmm_kernel2(const SsmmArgs
           }
           continue;
         }
-        uint32_t o[8 * NP];
-#pragma unroll
-        for (int q = 0; q < 8 * NP; q++)
-          o[q] = VEC ? cvt_bf16x2(value(0, q), value(1, q)) : cvt_bf16x2(value(0, 2 * q), value(0, 2 * q + 1));
         uint4* dst = (uint4*)(p.out + pos * p.rows + (tile * 32 + 16 * ph) * NP);
 #pragma unroll
-        for (int q = 0; q < 2 * NP; q++) dst[q] = make_uint4(o[4 * q], o[4 * q + 1], o[4 * q + 2], o[4 * q + 3]);
+        for (int half = 0; half < NP; half++) {   // 32 bytes at a time (registers)
+          uint32_t o[8];
+#pragma unroll
+          for (int q = 0; q < 8; q++) {
+            const int qq = half * 8 + q;
+            o[q] = VEC ? cvt_bf16x2(value(0, qq), value(1, qq)) : cvt_bf16x2(value(0, 2 * qq), value(0, 2 * qq + 1));
+          }
+          dst[2 * half] = make_uint4(o[0], o[1], o[2], o[3]);
+          dst[2 * half + 1] = make_uint4(o[4], o[5], o[6], o[7]);
+          if (VEC) __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
   };
@@ -1257,20 +1288,21 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) ssmm_kernel2(const SsmmArgs
       constexpr bool REL = !GATEUP && !VEC;
       const bool rel = REL && !p.sel;
       t.bbase = (const char*)p.act + (int64_t)ks0 * (2 * kStageK) + (rel ? (int64_t)cur.row0 * p.K * 2 : 0);
-      int src[CH];
-      rows_of(cur, src);
-#pragma unroll
-      for (int i = 0; i < CH; i++) {
-        const int slot = i * NTH + wv * 64 + ln, r = slot >> 3, c = (slot & 7) ^ (r & 7);
-        const int row = rel ? min(r, cur.nvalid - 1) : src[i];
-        t.vb[i] = (uint32_t)(((int64_t)row * p.K + c * 8) * 2);
-      }
+      transfer_offsets(rel);
       t.start(KS);
     }
     ln = lane_again();
     if (have_prev) epilogue();
     if (!have_cur) break;
     ln = lane_again();
+    // The kernels with the fewest registers to spare (vector-wise format on 160-token tiles) compute the
+    // per-lane offsets once more, so that they occupy no registers while the epilogue runs (the row ids
+    // are still in LDS: the rows of the tile after cur are requested below).
+    if constexpr (VEC && NT == 5) {
+      transfer_offsets(false);
+      operand_offsets(ln);
+      t.refresh_offsets(ln);
+    }
     Where next = {};
     li += nslots;
     const bool have_next = locate(li, next);
@@ -1561,10 +1593,27 @@ struct FfnPlan {
   int pipe, pipe_down;   // 2: hand-scheduled kernels, 1: compiler-scheduled ones
   int gshape;            // first product on the hand-scheduled kernels: tile class
   bool wide5;            //   ... and 160 instead of 128 tokens at the widest class
+  bool vec_gu5, vec_down5;   // (1,2,V) on the hand-scheduled kernels: 160- instead of 128-token tiles for the first product / the down projection
   int down_kernel;       // DownKernel (hand-scheduled kernels, plain 2:4)
   int splits, kper;      // slices of the down projection's reduction (1: whole sums), stages per slice
   size_t yp_off, extra_off, bytes;   // workspace: h at 0, yp, partial sums / expanded weights
 };
+
+// Expected number of NB-token tiles of a bucket: its size taken as normal around `mean` with variance `mean`
+// (balanced routing; the host never sees the real sizes): the sum over j of P(size > j NB).
+inline double expected_tiles(double mean, int NB) {
+  const double sd = sqrt(mean > 1.0 ? mean : 1.0);
+  double sum = 0.0;
+  for (int j = 0; j * (double)NB < mean + 6.0 * sd + NB; j++) sum += 0.5 * erfc((j * (double)NB - mean) / (sd * 1.4142135623730951));
+  return sum;
+}
+// Time of a launch whose equal tiles the resident blocks take in rounds, in units of one round: a last round
+// that is not full costs a full round unless it holds very few tiles (measured on the Mixtral shape, (1,2,8):
+// 0.04 of a round of tiles cost half a round, 0.125 a whole one).
+inline double rounds_cost(double tiles, int slots) {
+  const double r = tiles / slots, whole = floor(r), part = r - whole;
+  return whole + (part <= 0.01 ? 0.0 : fmin(1.0, 0.4 + 5.0 * part));
+}
 
 inline FfnPlan plan_ffn(int T, int H, int F, int E_total, int slots, ssmm_format f) {
   FfnPlan pl = {};
@@ -1617,6 +1666,12 @@ inline FfnPlan plan_ffn(int T, int H, int F, int E_total, int slots, ssmm_format
     const double pad4 = ceil(est / 128.0) * 128.0, pad5 = ceil(est / 160.0) * 160.0;
     pl.wide5 = pad5 <= 1.1 * pad4;
     if (const int want = knob("SSMM_GU_NT5"); want != kUnset) pl.wide5 = want == 1;
+    // (1,2,V): the same choice, on the expected tile counts (measured on the Mixtral shape, (1,2,8), first
+    // product: 15 % faster at 512 tokens, 6 % at 1024, 4.5 % at 8192, equal at 4096 -- and 5 % slower at 2048,
+    // where 4.5 tiles of 128 stand against 4 of 160)
+    const double mean = (double)P / (double)active;
+    pl.vec_gu5 = pl.vec && pl.gshape >= 1 && expected_tiles(mean, 160) * 160.0 <= 1.1 * expected_tiles(mean, 128) * 128.0;
+    if (const int want = knob("SSMM_VEC_GU_NT5"); want != kUnset) pl.vec_gu5 = pl.vec && pl.gshape >= 1 && want == 1;
   }
 
   // ---- down projection
@@ -1658,6 +1713,14 @@ inline FfnPlan plan_ffn(int T, int H, int F, int E_total, int slots, ssmm_format
       }
     } else if (shape == 2) {
       splits = 1;
+      // (1,2,V), large buckets: 512 dense rows x 128 or 160 tokens per block.  The 160-token tile takes 5/4 of
+      // the time of a 128-token one; what decides is the number of rounds the resident blocks need (measured on
+      // the Mixtral shape, (1,2,8): 4096 tokens, 544 tiles of 128 = 3 rounds against 448 of 160 = 2: 0.55 -> 0.47 ms;
+      // 2048 tokens 0.35 -> 0.25 ms; 1024 and 6000 tokens the other way round, 0.18 / 0.20 and 0.63 / 0.72 ms)
+      const double mean = (double)P / (double)active, blocks = (double)active * ((H + 511) / 512);
+      const int cus = compute_units();
+      pl.vec_down5 = 5.0 * rounds_cost(blocks * expected_tiles(mean, 160), cus) <= 4.0 * rounds_cost(blocks * expected_tiles(mean, 128), cus);
+      if (const int want = knob("SSMM_VEC_DOWN_NT5"); want != kUnset) pl.vec_down5 = want == 1;
     }
   } else if (pl.gen && shape < 2 && P * F * 2 < (int64_t)1 << 32) {
     // small buckets: few rows per block and the reduction split, so that every CU has blocks to
@@ -1835,7 +1898,8 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
            : pl.gshape == 1           ? launch_ssmm2<true, false, 1, 4, 4, 1, 4>(g, P, s)
                                       : launch_ssmm2<true, false, 1, 1, 4, 1, 4, 2>(g, P, s);
     else if (pipe != 1)
-      st = pl.gshape >= 1 ? launch_ssmm2<true, true, 1, 4, 4, 1, 4>(g, P, s) : launch_ssmm2<true, true, 1, 1, 4, 1, 4>(g, P, s);
+      st = pl.gshape >= 1 ? (pl.vec_gu5 ? launch_ssmm2<true, true, 1, 5, 4, 1, 3>(g, P, s) : launch_ssmm2<true, true, 1, 4, 4, 1, 4>(g, P, s))
+                          : launch_ssmm2<true, true, 1, 1, 4, 1, 4>(g, P, s);
     else if (!vec)   // fall-back kernels: 128-, 64- and 32-token tiles
       st = shape == 2   ? launch_ssmm<true, false, 2, 4, 4, 1, 3>(g, P, s)
            : shape == 1 ? launch_ssmm<true, false, 2, 2, 4, 1, 3>(g, P, s)
@@ -1900,7 +1964,7 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
         st = split ? launch_ssmm2<false, false, 2, 1, 4, 1, 4, 2, true>(d, P, s) : launch_ssmm2<false, false, 2, 1, 4, 1, 4, 2>(d, P, s);
     }
   } else if (pl.pipe_down != 1) {
-    st = shape == 2   ? launch_ssmm2<false, true, 2, 4, 4, 1, 4>(d, P, s)
+    st = shape == 2   ? (pl.vec_down5 ? launch_ssmm2<false, true, 2, 5, 4, 1, 3>(d, P, s) : launch_ssmm2<false, true, 2, 4, 4, 1, 4>(d, P, s))
          : shape == 1 ? (split ? launch_ssmm2<false, true, 1, 4, 4, 1, 4, 1, true>(d, P, s)
                                : launch_ssmm2<false, true, 1, 4, 4, 1, 4>(d, P, s))
                       : (split ? launch_ssmm2<false, true, 1, 1, 4, 1, 4, 2, true>(d, P, s)

@@ -425,3 +425,28 @@ def test_seeded_sweep_with_many_experts_matches_oracle(cfg, act, gated):
     err = G.rel_fro(G.bf16_tensor_to_f64(y), ref["y"])
     print(f"  rel_fro={err:.3e}", flush=True)
     assert err <= G.TOL, err
+
+
+# ---- (1,2,V) on 160-token tiles: the plan takes them by expected tile and round counts; here they are forced, so
+# ---- that every shape below runs both products on them (and, without the knobs, on whatever the plan takes) ----
+VEC160_CASES = [
+    LayerConfig("vec160_two_tiles", T=1300, H=512, F=768, E=4, topk=2, fmt=(1, 2, 8), seed=141),                  # ~650 pairs per expert: ragged fifth tile
+    LayerConfig("vec160_shared", T=3000, H=1024, F=512, E=3, topk=1, S=1, fmt=(1, 2, 16), renormalize=False, seed=142),
+    LayerConfig("vec160_odd_rows", T=2000, H=640, F=448, E=2, topk=2, fmt=(1, 2, 32), seed=143),                  # row tiles that do not fill a block
+    LayerConfig("vec160_many_experts", T=2000, H=256, F=512, E=40, topk=8, fmt=(1, 2, 8), logits="biased", seed=144),
+    LayerConfig("vec160_loop", T=7000, H=1024, F=1024, E=4, topk=2, fmt=(1, 2, 8), seed=145),                    # more tiles than resident blocks
+]
+
+
+@pytest.mark.parametrize("cfg", VEC160_CASES, ids=[c.name for c in VEC160_CASES])
+def test_vector_wise_format_on_160_token_tiles(monkeypatch, tuning_library, cfg):
+    monkeypatch.setenv("SSMM_VEC_GU_NT5", "1")
+    monkeypatch.setenv("SSMM_VEC_DOWN_NT5", "1")
+    monkeypatch.setenv("SSMM_TILE_SHAPE", "2")          # the large-bucket rules, whatever the bucket size
+    got, ref, err = run_case(cfg)
+    monkeypatch.setenv("SSMM_VEC_GU_NT5", "0")
+    monkeypatch.setenv("SSMM_VEC_DOWN_NT5", "0")
+    y, _ = G.run_gpu_layer(cfg, *G.make_inputs(cfg))     # the 128-token tiles on the same inputs
+    d = G.rel_fro(G.bf16_tensor_to_f64(y), got)
+    print(f"  160- vs 128-token tiles rel_fro={d:.3e}", flush=True)
+    assert d == 0.0      # same products in the same order: the tile width changes no sum
