@@ -1295,11 +1295,11 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) ssmm_kernel2(const SsmmArgs
     if (have_prev) epilogue();
     if (!have_cur) break;
     ln = lane_again();
-    // The kernels with the fewest registers to spare (vector-wise format on 160-token tiles) compute the
+    // The kernels with the fewest registers to spare (vector-wise format on 160-token tiles, 512 x 128 tiles) compute the
     // per-lane offsets once more, so that they occupy no registers while the epilogue runs (the row ids
     // are still in LDS: the rows of the tile after cur are requested below).
-    if constexpr (VEC && NT == 5) {
-      transfer_offsets(false);
+    if constexpr ((VEC && NT == 5) || (!GATEUP && !VEC && MT == 4 && NT == 4)) {
+      transfer_offsets((!GATEUP && !VEC) && !p.sel);
       operand_offsets(ln);
       t.refresh_offsets(ln);
     }
@@ -1582,7 +1582,7 @@ inline bool expands_weights(ssmm_format f, int64_t P, int E_total) {
 #ifndef SKIP_NT
 #define SKIP_NT 2   // token tiles of 32 per wave on the compute-skipping kernels (their accumulators live in vector registers)
 #endif
-enum DownKernel { kDownSmall, kDownMedium, kDownMedium5, kDownHalf, kDownTall };
+enum DownKernel { kDownSmall, kDownMedium, kDownMedium5, kDownHalf, kDownTall, kDownTall4 };
 struct FfnPlan {
   int64_t P;
   bool expanded;         // gathered format multiplied as plain 2:4 operands expanded into the workspace
@@ -1709,7 +1709,18 @@ inline FfnPlan plan_ffn(int T, int H, int F, int E_total, int slots, ssmm_format
         splits = 1;
       } else {
         pl.down_kernel = dshape == 2 ? kDownTall : dshape == 1 ? kDownMedium : kDownSmall;
-        if (dshape == 2) splits = 1;
+        if (dshape == 2) {
+          splits = 1;
+          // 512 rows x 160 or 128 tokens per block, by the rounds the resident blocks need (the 160-token tile
+          // takes 5/4 of the time of the 128-token one): measured on the Mixtral shape, the down projection is a
+          // staircase in the token count -- 0.26 ms up to 2304 tokens (256 tiles of 160: one round), 0.47-0.51 from
+          // 2560 to 4608 (two), 0.73-0.81 from 5120 to 7168 (three) -- and the other width often needs a round less
+          const double mean = (double)P / (double)active, blocks = (double)active * ((H + 511) / 512);
+          const int cus = compute_units();
+          bool tall4 = 4.0 * rounds_cost(blocks * expected_tiles(mean, 128), cus) < 5.0 * rounds_cost(blocks * expected_tiles(mean, 160), cus);
+          if (const int want = knob("SSMM_DOWN_TALL_NT4"); want != kUnset) tall4 = want == 1;
+          if (tall4) pl.down_kernel = kDownTall4;
+        }
       }
     } else if (shape == 2) {
       splits = 1;
@@ -1956,6 +1967,9 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
         break;
       case kDownTall:
         st = split ? launch_ssmm2<false, false, 4, 5, 4, 1, 3, 1, true>(d, P, s) : launch_ssmm2<false, false, 4, 5, 4, 1, 3>(d, P, s);
+        break;
+      case kDownTall4:
+        st = launch_ssmm2<false, false, 4, 4, 4, 1, 3>(d, P, s);
         break;
       case kDownMedium:
         st = split ? launch_ssmm2<false, false, 2, 4, 4, 1, 4, 1, true>(d, P, s) : launch_ssmm2<false, false, 2, 4, 4, 1, 4>(d, P, s);

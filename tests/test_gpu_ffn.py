@@ -450,3 +450,22 @@ def test_vector_wise_format_on_160_token_tiles(monkeypatch, tuning_library, cfg)
     d = G.rel_fro(G.bf16_tensor_to_f64(y), got)
     print(f"  160- vs 128-token tiles rel_fro={d:.3e}", flush=True)
     assert d == 0.0      # same products in the same order: the tile width changes no sum
+
+
+# ---- plain 2:4, large buckets: the down projection on 512-row x 128-token tiles (the plan takes them when they
+# ---- need a round of the resident blocks less than the 160-token ones); forced here ----
+TALL128_CASES = [
+    LayerConfig("tall128_two_tiles", T=1300, H=512, F=768, E=4, topk=2, seed=151),
+    LayerConfig("tall128_odd_rows", T=3000, H=1088, F=512, E=3, topk=1, S=1, renormalize=False, seed=152),   # 34 row tiles: the last block half empty
+    LayerConfig("tall128_loop", T=7000, H=2048, F=1024, E=4, topk=2, seed=153),                              # more tiles than resident blocks
+]
+
+
+@pytest.mark.parametrize("cfg", TALL128_CASES, ids=[c.name for c in TALL128_CASES])
+def test_down_projection_on_512_by_128_tiles(monkeypatch, tuning_library, cfg):
+    monkeypatch.setenv("SSMM_TILE_SHAPE", "2")
+    monkeypatch.setenv("SSMM_DOWN_TALL_NT4", "1")
+    got, ref, err = run_case(cfg)
+    monkeypatch.setenv("SSMM_DOWN_TALL_NT4", "0")
+    y, _ = G.run_gpu_layer(cfg, *G.make_inputs(cfg))     # the 160-token tiles on the same inputs
+    assert G.rel_fro(G.bf16_tensor_to_f64(y), got) == 0.0   # the tile width changes no sum
