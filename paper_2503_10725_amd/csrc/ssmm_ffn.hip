@@ -1666,11 +1666,12 @@ inline FfnPlan plan_ffn(int T, int H, int F, int E_total, int slots, ssmm_format
     const double pad4 = ceil(est / 128.0) * 128.0, pad5 = ceil(est / 160.0) * 160.0;
     pl.wide5 = pad5 <= 1.1 * pad4;
     if (const int want = knob("SSMM_GU_NT5"); want != kUnset) pl.wide5 = want == 1;
-    // (1,2,V): the same choice, on the expected tile counts (measured on the Mixtral shape, (1,2,8), first
-    // product: 15 % faster at 512 tokens, 6 % at 1024, 4.5 % at 8192, equal at 4096 -- and 5 % slower at 2048,
-    // where 4.5 tiles of 128 stand against 4 of 160)
+    // (1,2,V): the same choice, on the expected tile counts and with 5 % (measured on the Mixtral shape, (1,2,8),
+    // first product: 15 % faster at 512 tokens, 6 % at 1024, 4.5 % at 8192, equal at 4096 -- and 5 % slower at
+    // 2048, where 4.5 tiles of 128 stand against 4 of 160; DeepSeek-shaped with two shared experts, 2048 tokens:
+    // 12 % slower, the routed buckets of 192 pad to 320)
     const double mean = (double)P / (double)active;
-    pl.vec_gu5 = pl.vec && pl.gshape >= 1 && expected_tiles(mean, 160) * 160.0 <= 1.1 * expected_tiles(mean, 128) * 128.0;
+    pl.vec_gu5 = pl.vec && pl.gshape >= 1 && expected_tiles(mean, 160) * 160.0 <= 1.05 * expected_tiles(mean, 128) * 128.0;
     if (const int want = knob("SSMM_VEC_GU_NT5"); want != kUnset) pl.vec_gu5 = pl.vec && pl.gshape >= 1 && want == 1;
   }
 
@@ -1717,7 +1718,9 @@ inline FfnPlan plan_ffn(int T, int H, int F, int E_total, int slots, ssmm_format
           // 2560 to 4608 (two), 0.73-0.81 from 5120 to 7168 (three) -- and the other width often needs a round less
           const double mean = (double)P / (double)active, blocks = (double)active * ((H + 511) / 512);
           const int cus = compute_units();
-          bool tall4 = 4.0 * rounds_cost(blocks * expected_tiles(mean, 128), cus) < 5.0 * rounds_cost(blocks * expected_tiles(mean, 160), cus);
+          // (long reductions only: with 22 or 40 stages per tile -- DeepSeek-, Qwen-shaped -- a tile's time hardly
+          // depends on its width, the 160-token tiles are fewer, and they were 3-10 % faster at every token count)
+          bool tall4 = KS >= 128 && 4.0 * rounds_cost(blocks * expected_tiles(mean, 128), cus) < 5.0 * rounds_cost(blocks * expected_tiles(mean, 160), cus);
           if (const int want = knob("SSMM_DOWN_TALL_NT4"); want != kUnset) tall4 = want == 1;
           if (tall4) pl.down_kernel = kDownTall4;
         }
@@ -1730,7 +1733,10 @@ inline FfnPlan plan_ffn(int T, int H, int F, int E_total, int slots, ssmm_format
       // 2048 tokens 0.35 -> 0.25 ms; 1024 and 6000 tokens the other way round, 0.18 / 0.20 and 0.63 / 0.72 ms)
       const double mean = (double)P / (double)active, blocks = (double)active * ((H + 511) / 512);
       const int cus = compute_units();
-      pl.vec_down5 = 5.0 * rounds_cost(blocks * expected_tiles(mean, 160), cus) <= 4.0 * rounds_cost(blocks * expected_tiles(mean, 128), cus);
+      // (short reductions -- 22 or 40 stages per tile on the DeepSeek- and Qwen-shaped layers: a tile's time hardly
+      // depends on its width there, so the width that pads less)
+      pl.vec_down5 = KS >= 128 ? 5.0 * rounds_cost(blocks * expected_tiles(mean, 160), cus) <= 4.0 * rounds_cost(blocks * expected_tiles(mean, 128), cus)
+                               : expected_tiles(mean, 160) * 160.0 <= 1.05 * expected_tiles(mean, 128) * 128.0;
       if (const int want = knob("SSMM_VEC_DOWN_NT5"); want != kUnset) pl.vec_down5 = want == 1;
     }
   } else if (pl.gen && shape < 2 && P * F * 2 < (int64_t)1 << 32) {
