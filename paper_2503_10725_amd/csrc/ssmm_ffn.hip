@@ -1603,8 +1603,10 @@ struct FfnPlan {
 // (balanced routing; the host never sees the real sizes): the sum over j of P(size > j NB).
 inline double expected_tiles(double mean, int NB) {
   const double sd = sqrt(mean > 1.0 ? mean : 1.0);
-  double sum = 0.0;
-  for (int j = 0; j * (double)NB < mean + 6.0 * sd + NB; j++) sum += 0.5 * erfc((j * (double)NB - mean) / (sd * 1.4142135623730951));
+  // every term more than six standard deviations below the mean is 1, every one as far above it 0
+  const double first = floor((mean - 6.0 * sd) / NB);
+  double sum = first > 0.0 ? first : 0.0;
+  for (double j = sum; j * NB < mean + 6.0 * sd; j += 1.0) sum += 0.5 * erfc((j * NB - mean) / (sd * 1.4142135623730951));
   return sum;
 }
 // Time of a launch whose equal tiles the resident blocks take in rounds, in units of one round: a last round
