@@ -1593,6 +1593,7 @@ struct FfnPlan {
   int pipe, pipe_down;   // 2: hand-scheduled kernels, 1: compiler-scheduled ones
   int gshape;            // first product on the hand-scheduled kernels: tile class
   bool wide5;            //   ... and 160 instead of 128 tokens at the widest class
+  bool gu_nt2;           //   ... or 64 tokens, for buckets that fit them
   bool vec_gu5, vec_down5;   // (1,2,V) on the hand-scheduled kernels: 160- instead of 128-token tiles for the first product / the down projection
   int down_kernel;       // DownKernel (hand-scheduled kernels, plain 2:4)
   int splits, kper;      // slices of the down projection's reduction (1: whole sums), stages per slice
@@ -1668,6 +1669,11 @@ inline FfnPlan plan_ffn(int T, int H, int F, int E_total, int slots, ssmm_format
     const double pad4 = ceil(est / 128.0) * 128.0, pad5 = ceil(est / 160.0) * 160.0;
     pl.wide5 = pad5 <= 1.1 * pad4;
     if (const int want = knob("SSMM_GU_NT5"); want != kUnset) pl.wide5 = want == 1;
+    // ... and 64-token tiles while a bucket somewhat above the mean fits one: the weights stream once either way
+    // and half the token-tile transfers and MFMAs go (measured: Qwen-shaped layer, 256 tokens, 0.234 -> 0.219 ms;
+    // Mixtral shape, 128 tokens, 0.191 -> 0.187; equal at 16 to 64 tokens, where the weight stream alone counts)
+    pl.gu_nt2 = !pl.vec && pl.gshape == 2 && !pl.wide5 && est <= 64.0;
+    if (const int want = knob("SSMM_GU_NT2"); want != kUnset) pl.gu_nt2 = !pl.vec && pl.gshape == 2 && !pl.wide5 && want == 1;
     // (1,2,V): the same choice, on the expected tile counts and with 5 % (measured on the Mixtral shape, (1,2,8),
     // first product: 15 % faster at 512 tokens, 6 % at 1024, 4.5 % at 8192, equal at 4096 -- and 5 % slower at
     // 2048, where 4.5 tiles of 128 stand against 4 of 160; DeepSeek-shaped with two shared experts, 2048 tokens:
@@ -1913,6 +1919,7 @@ extern "C" int ssmm_expert_ffn_variant(const uint16_t* x, int T, int H, int F, i
                       : launch_ssmm<true, false, 1, 1, 4, 1, 3, true>(g, P, s);
     else if (pipe != 1 && !vec)
       st = pl.gshape == 2 && pl.wide5 ? launch_ssmm2<true, false, 2, 5, 4, 1, 3>(g, P, s)
+           : pl.gshape == 2 && pl.gu_nt2 ? launch_ssmm2<true, false, 2, 2, 4, 1, 4>(g, P, s)
            : pl.gshape == 2           ? launch_ssmm2<true, false, 2, 4, 4, 1, 4>(g, P, s)
            : pl.gshape == 1           ? launch_ssmm2<true, false, 1, 4, 4, 1, 4>(g, P, s)
                                       : launch_ssmm2<true, false, 1, 1, 4, 1, 4, 2>(g, P, s);

@@ -469,3 +469,18 @@ def test_down_projection_on_512_by_128_tiles(monkeypatch, tuning_library, cfg):
     monkeypatch.setenv("SSMM_DOWN_TALL_NT4", "0")
     y, _ = G.run_gpu_layer(cfg, *G.make_inputs(cfg))     # the 160-token tiles on the same inputs
     assert G.rel_fro(G.bf16_tensor_to_f64(y), got) == 0.0   # the tile width changes no sum
+
+
+@pytest.mark.parametrize("cfg", [LayerConfig("gu64_small", T=40, H=512, F=1024, E=8, topk=2, seed=161),
+                                 LayerConfig("gu64_two_tiles", T=300, H=256, F=768, E=6, topk=2, S=1, seed=162),      # the shared expert needs five tiles of 64
+                                 LayerConfig("gu64_odd_rows", T=200, H=1024, F=448, E=3, topk=1, seed=163)], ids=lambda c: c.name)
+def test_first_product_on_256_by_64_tiles(monkeypatch, tuning_library, cfg):
+    """The 64-token version of the widest gate/up tile (the plan takes it for small buckets of layers with many
+    row tiles), forced here on small layers; the tile width changes no sum."""
+    monkeypatch.setenv("SSMM_GU_SHAPE", "2")
+    monkeypatch.setenv("SSMM_GU_NT5", "0")
+    monkeypatch.setenv("SSMM_GU_NT2", "1")
+    got, ref, err = run_case(cfg)
+    monkeypatch.setenv("SSMM_GU_NT2", "0")
+    y, _ = G.run_gpu_layer(cfg, *G.make_inputs(cfg))     # the 128-token tiles on the same inputs
+    assert G.rel_fro(G.bf16_tensor_to_f64(y), got) == 0.0
